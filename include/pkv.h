@@ -1,0 +1,227 @@
+/*
+ * pkv.h - C ABI of the ProphetKV selective-recomputation hot path for
+ *         AMD MI355X (gfx950).
+ *
+ * ProphetKV (arXiv 2602.02579) reuses chunk-wise precomputed KV caches in
+ * RAG prefill and repairs them by recomputing only the context tokens the
+ * user query attends to.  Per transformer layer the hot path is:
+ *
+ *   1. pkv_rope_restore     put positions back on the assembled,
+ *                           position-free chunk keys
+ *   2. pkv_query_score      attention of the user-query tokens to every
+ *                           context token, averaged over heads and query
+ *                           tokens, summed over layers
+ *   3. pkv_topk_select      the top p-fraction of context tokens
+ *   4. pkv_gather_qkv_proj  Q/K/V projection + rotation of the selected and
+ *      pkv_scatter_kv       the query rows; new K/V replace the cache rows
+ *   5. pkv_sparse_row_attn  causal attention of those rows over the cache
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ * Pointers: `cfg` is a host pointer, read during the call only.  Every other
+ *   pointer is a DEVICE pointer to memory owned by the caller; the library
+ *   allocates nothing, frees nothing and keeps no pointer after the call
+ *   returns.  Scratch memory is caller-provided (`ws`, `ws_bytes`), sized by
+ *   pkv_workspace_bytes(), 256-byte aligned, and may be reused between calls
+ *   on the same stream.
+ * Layout: token-major, contiguous.  Keys/values [tokens, n_kv_heads,
+ *   head_dim]; queries/outputs [rows, n_q_heads, head_dim]; hidden states
+ *   [tokens, hidden]; weights [out_features, hidden] (row-major, so both
+ *   GEMM operands have the contraction dimension contiguous).  Element type
+ *   is cfg->dtype (fp32 or bf16) for every tensor typed `void*`; scores and
+ *   log-sum-exp are always fp32, indices and positions int32.
+ * Heads: query head h reads kv head h / (n_q_heads / n_kv_heads).
+ * Rotary embedding: element i < D/2 of a head is paired with element
+ *   i + D/2 and turned by position * rope_theta^(-2i/D); no frequency
+ *   scaling.
+ * Streams: `stream` is a hipStream_t passed as void* (NULL = the null
+ *   stream).  Calls enqueue work and return without synchronising.
+ * Errors: arguments that the host can check (null pointers, non-positive or
+ *   inconsistent sizes, unsupported dtype or head_dim, workspace too small)
+ *   give an error code and enqueue nothing.  A failed launch gives
+ *   PKV_ERR_LAUNCH.  Not checked (undefined results, but no out-of-bounds
+ *   access is made on their account unless stated): non-finite inputs.
+ *   Index arrays (row_idx, dst_row, row_pos) are read on the device, so
+ *   their VALUES cannot be checked by the host: out-of-range values there
+ *   are undefined behaviour and are the caller's responsibility.
+ * Supported shapes: head_dim even, a multiple of 16 and <= 256;
+ *   n_q_heads a multiple of n_kv_heads; hidden a multiple of 8.
+ */
+#ifndef PKV_H
+#define PKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PKV_OK = 0,
+    PKV_ERR_NULL = 1,        /* a required pointer is NULL               */
+    PKV_ERR_SHAPE = 2,       /* a size is negative / inconsistent        */
+    PKV_ERR_UNSUPPORTED = 3, /* dtype / head_dim / geometry not built    */
+    PKV_ERR_WORKSPACE = 4,   /* ws is NULL or ws_bytes is too small      */
+    PKV_ERR_LAUNCH = 5       /* the HIP runtime refused a launch         */
+} pkv_status;
+
+typedef enum { PKV_F32 = 0, PKV_BF16 = 1 } pkv_dtype;
+
+typedef struct {
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t hidden;
+    float   rope_theta;
+    int32_t dtype;           /* pkv_dtype: storage type of all void* tensors */
+} pkv_layer_cfg;
+
+/* which_call values for pkv_workspace_bytes */
+enum {
+    PKV_CALL_ROPE_RESTORE = 1,
+    PKV_CALL_QUERY_SCORE = 2,
+    PKV_CALL_TOPK_SELECT = 3,
+    PKV_CALL_GATHER_QKV_PROJ = 4,
+    PKV_CALL_SCATTER_KV = 5,
+    PKV_CALL_SPARSE_ROW_ATTN = 6
+};
+
+/*
+ * Step 1 - rotary position restore (paper: Sec. 1 footnote on
+ * position-independent caches; Appendix E, closing paragraph: positions are
+ * applied to the old key cache exactly once, before cache replacement;
+ * Algorithm 1, concatenation of the chunk caches).
+ *
+ * k_out[t, g, :] = R(p_t) k_in[t, g, :] for t < n, every kv head g, where
+ * p_t = pos[t] if pos != NULL else pos_base + t.  Positions may be negative
+ * (the inverse rotation).  k_out may alias k_in exactly (in place); partial
+ * overlap is not allowed.  The result is rounded once to cfg->dtype.
+ * n == 0 is a no-op.
+ */
+pkv_status pkv_rope_restore(const pkv_layer_cfg* cfg,
+                            const void* k_in,   /* [n, Hkv, D] */
+                            void* k_out,        /* [n, Hkv, D] */
+                            const int32_t* pos, /* [n] or NULL */
+                            int64_t pos_base, int64_t n, void* stream);
+
+/*
+ * Step 2 - query-driven value function (paper: Algorithm 1, first stage:
+ * alpha_l = Softmax(Q_s K'^T / sqrt(d_k)); Sec. 4.2: average over the query
+ * tokens; Appendix E: mean over heads; Algorithm 1 second stage / Eq. 7:
+ * fusion over layers is a sum).
+ *
+ * score[t] (+)= 1/(Hq*nq) * sum_{h, q} softmax_t(q[q,h] . k[t,g(h)] * scale)
+ * with the softmax running over the n_ctx context keys only.  `q` holds the
+ * rotated user-query queries, `k` the restored context keys.  With
+ * accumulate == 0 the score is overwritten, otherwise the new layer is added
+ * to it (fp32).  softmax_scale == 0 means 1/sqrt(D).  Deterministic: the
+ * same inputs give the same bits.
+ */
+pkv_status pkv_query_score(const pkv_layer_cfg* cfg,
+                           const void* q,      /* [nq, Hq, D]     */
+                           const void* k,      /* [n_ctx, Hkv, D] */
+                           float* score,       /* [n_ctx]         */
+                           int64_t nq, int64_t n_ctx, float softmax_scale,
+                           int accumulate, void* ws, size_t ws_bytes,
+                           void* stream);
+
+/*
+ * Step 3 - top-p selection (paper: Eq. 4, TOP_p of the value function;
+ * Algorithm 1 "Select token indices"; Sec. 4.3: one set for all layers).
+ *
+ * idx_out receives the indices of the k largest scores in ascending index
+ * order.  Among equal scores the lower index is taken first, so the result
+ * is unique.  -0.0 and +0.0 compare equal.  k == 0 writes nothing; k == n
+ * writes 0..n-1.  Scores must be finite.
+ */
+pkv_status pkv_topk_select(const float* score, /* [n] */
+                           int64_t n, int64_t k,
+                           int32_t* idx_out,   /* [k] */
+                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Step 4a - gather, project, rotate (paper: Algorithm 1 "Recompute KV cache
+ * at layer l" and "Calculate user query KV cache"; Appendix E, third step:
+ * hidden states and positions are pruned to the selected tokens).
+ *
+ * For i < m: x = hidden[row_idx ? row_idx[i] : i, :];
+ *   q_out[i] = R(row_pos[i]) (Wq x),  k_out[i] = R(row_pos[i]) (Wk x),
+ *   v_out[i] = Wv x,
+ * fp32 accumulation, one rounding to cfg->dtype after the rotation.
+ * q_out may be NULL (then only K and V are produced); k_out and v_out may
+ * both be NULL (then only Q is produced).  row_idx values must lie in
+ * [0, n_hidden_rows) (checked only against negative m / null pointers on
+ * the host).  m == 0 is a no-op.
+ */
+pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg,
+                               const void* hidden,     /* [n_hidden_rows, hidden] */
+                               const int32_t* row_idx, /* [m] or NULL */
+                               const int32_t* row_pos, /* [m] */
+                               const void* wq,         /* [Hq*D, hidden]  */
+                               const void* wk,         /* [Hkv*D, hidden] */
+                               const void* wv,         /* [Hkv*D, hidden] */
+                               void* q_out,            /* [m, Hq, D]  */
+                               void* k_out,            /* [m, Hkv, D] */
+                               void* v_out,            /* [m, Hkv, D] */
+                               int64_t m, void* stream);
+
+/*
+ * Step 4b - cache update (paper: Algorithm 1 "Update layer-wise KV cache":
+ * rows in T_p take the recomputed K/V, all other rows are reused as they
+ * are; the user-query K/V are appended after the context).
+ *
+ * k_cache[dst_row[i]] = k_new[i], v_cache[dst_row[i]] = v_new[i] for i < m.
+ * dst_row values must be unique and lie in [0, n_cache).  No other cache row
+ * is touched.  m == 0 is a no-op.
+ */
+pkv_status pkv_scatter_kv(const pkv_layer_cfg* cfg,
+                          const void* k_new,      /* [m, Hkv, D] */
+                          const void* v_new,      /* [m, Hkv, D] */
+                          const int32_t* dst_row, /* [m] */
+                          void* k_cache,          /* [n_cache, Hkv, D] */
+                          void* v_cache,          /* [n_cache, Hkv, D] */
+                          int64_t m, int64_t n_cache, void* stream);
+
+/*
+ * Step 5 - attention of the recomputed rows over the whole updated cache
+ * (paper: Sec. 4.3 Stage II: complete recomputation across all layers, but
+ * only for the selected tokens; Sec. 5.3: this attention dominates the
+ * cost; Eq. 1 for the attention output).
+ *
+ * out[i, h] = sum_{t <= row_pos[i]} softmax_t(q[i,h] . k_cache[t,g(h)] * scale)
+ *             * v_cache[t, g(h)],
+ * i < m, fp32 softmax and accumulation, one rounding to cfg->dtype.
+ * row_pos[i] must lie in [0, n_keys); rows need not be sorted, but sorted
+ * rows (the order step 3 returns) give balanced tiles.  lse_out, if not
+ * NULL, receives the natural-log normaliser per (row, head).
+ * softmax_scale == 0 means 1/sqrt(D).  m == 0 is a no-op.
+ */
+pkv_status pkv_sparse_row_attn(const pkv_layer_cfg* cfg,
+                               const void* q,          /* [m, Hq, D] */
+                               const void* k_cache,    /* [n_keys, Hkv, D] */
+                               const void* v_cache,    /* [n_keys, Hkv, D] */
+                               const int32_t* row_pos, /* [m] */
+                               void* out,              /* [m, Hq, D] */
+                               float* lse_out,         /* [m, Hq] or NULL */
+                               int64_t m, int64_t n_keys, float softmax_scale,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Scratch bytes the given call needs for a problem with `n` cache/context
+ * tokens and `m` rows (query tokens for PKV_CALL_QUERY_SCORE).  Pure host
+ * function; returns 0 for calls that need none and for invalid arguments.
+ */
+size_t pkv_workspace_bytes(int which_call, const pkv_layer_cfg* cfg,
+                           int64_t n, int64_t m);
+
+/* Static, never-NULL description of a status code. */
+const char* pkv_status_string(pkv_status status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int pkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PKV_H */

@@ -1,0 +1,150 @@
+// C ABI of the library: host-side argument checks and dispatch to the kernel
+// launchers.  Nothing here touches device memory or synchronises.
+#include "pkv_common.h"
+
+#include <cmath>
+
+using namespace pkv;
+
+namespace {
+
+constexpr int64_t kMaxTokens = (int64_t)1 << 30;  // indices are int32
+
+pkv_status check_cfg(const pkv_layer_cfg* cfg) {
+    if (!cfg) return PKV_ERR_NULL;
+    if (cfg->dtype != PKV_F32 && cfg->dtype != PKV_BF16) return PKV_ERR_UNSUPPORTED;
+    if (cfg->n_q_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->head_dim <= 0 ||
+        cfg->hidden <= 0)
+        return PKV_ERR_SHAPE;
+    if (cfg->n_q_heads % cfg->n_kv_heads) return PKV_ERR_SHAPE;
+    if (cfg->head_dim % 16 || cfg->head_dim > 2 * kMaxHalfDim) return PKV_ERR_UNSUPPORTED;
+    if (cfg->hidden % 8) return PKV_ERR_UNSUPPORTED;
+    if (cfg->n_q_heads + 2 * cfg->n_kv_heads > 65535) return PKV_ERR_UNSUPPORTED;
+    if (!(cfg->rope_theta > 0.f) || !std::isfinite(cfg->rope_theta)) return PKV_ERR_SHAPE;
+    return PKV_OK;
+}
+
+float resolve_scale(float s, int head_dim) {
+    return s == 0.f ? 1.0f / std::sqrt((float)head_dim) : s;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+pkv_status pkv_rope_restore(const pkv_layer_cfg* cfg, const void* k_in,
+                            void* k_out, const int32_t* pos, int64_t pos_base,
+                            int64_t n, void* stream) {
+    pkv_status st = check_cfg(cfg);
+    if (st != PKV_OK) return st;
+    if (n < 0 || n > kMaxTokens) return PKV_ERR_SHAPE;
+    if (n == 0) return PKV_OK;
+    if (!k_in || !k_out) return PKV_ERR_NULL;
+    if (!pos && (pos_base < -kMaxTokens || pos_base > kMaxTokens)) return PKV_ERR_SHAPE;
+    return launch_rope_restore(*cfg, k_in, k_out, pos, pos_base, n, (hipStream_t)stream);
+}
+
+pkv_status pkv_query_score(const pkv_layer_cfg* cfg, const void* q, const void* k,
+                           float* score, int64_t nq, int64_t n_ctx,
+                           float softmax_scale, int accumulate, void* ws,
+                           size_t ws_bytes, void* stream) {
+    pkv_status st = check_cfg(cfg);
+    if (st != PKV_OK) return st;
+    if (nq <= 0 || n_ctx <= 0 || n_ctx > kMaxTokens || nq > (1 << 20)) return PKV_ERR_SHAPE;
+    if (!q || !k || !score) return PKV_ERR_NULL;
+    if (!std::isfinite(softmax_scale) || softmax_scale < 0.f) return PKV_ERR_SHAPE;
+    const size_t need = align256(query_score_ws_bytes(*cfg, n_ctx, nq));
+    if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
+    return launch_query_score(*cfg, q, k, score, nq, n_ctx,
+                              resolve_scale(softmax_scale, cfg->head_dim), accumulate,
+                              ws, (hipStream_t)stream);
+}
+
+pkv_status pkv_topk_select(const float* score, int64_t n, int64_t k,
+                           int32_t* idx_out, void* ws, size_t ws_bytes,
+                           void* stream) {
+    (void)ws; (void)ws_bytes;
+    if (n < 0 || n > kMaxTokens || k < 0 || k > n) return PKV_ERR_SHAPE;
+    if (k == 0) return PKV_OK;
+    if (!score || !idx_out) return PKV_ERR_NULL;
+    return launch_topk_select(score, n, k, idx_out, (hipStream_t)stream);
+}
+
+pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg, const void* hidden,
+                               const int32_t* row_idx, const int32_t* row_pos,
+                               const void* wq, const void* wk, const void* wv,
+                               void* q_out, void* k_out, void* v_out, int64_t m,
+                               void* stream) {
+    pkv_status st = check_cfg(cfg);
+    if (st != PKV_OK) return st;
+    if (m < 0 || m > kMaxTokens) return PKV_ERR_SHAPE;
+    if (m == 0) return PKV_OK;
+    if (!hidden || !row_pos) return PKV_ERR_NULL;
+    if ((k_out == nullptr) != (v_out == nullptr)) return PKV_ERR_NULL;
+    if (!q_out && !k_out) return PKV_ERR_NULL;
+    if (q_out && !wq) return PKV_ERR_NULL;
+    if (k_out && (!wk || !wv)) return PKV_ERR_NULL;
+    return launch_gather_qkv_proj(*cfg, hidden, row_idx, row_pos, wq, wk, wv, q_out,
+                                  k_out, v_out, m, (hipStream_t)stream);
+}
+
+pkv_status pkv_scatter_kv(const pkv_layer_cfg* cfg, const void* k_new,
+                          const void* v_new, const int32_t* dst_row, void* k_cache,
+                          void* v_cache, int64_t m, int64_t n_cache, void* stream) {
+    pkv_status st = check_cfg(cfg);
+    if (st != PKV_OK) return st;
+    if (m < 0 || n_cache < 0 || n_cache > kMaxTokens || m > n_cache) return PKV_ERR_SHAPE;
+    if (m == 0) return PKV_OK;
+    if (!k_new || !v_new || !dst_row || !k_cache || !v_cache) return PKV_ERR_NULL;
+    return launch_scatter_kv(*cfg, k_new, v_new, dst_row, k_cache, v_cache, m,
+                             (hipStream_t)stream);
+}
+
+pkv_status pkv_sparse_row_attn(const pkv_layer_cfg* cfg, const void* q,
+                               const void* k_cache, const void* v_cache,
+                               const int32_t* row_pos, void* out, float* lse_out,
+                               int64_t m, int64_t n_keys, float softmax_scale,
+                               void* ws, size_t ws_bytes, void* stream) {
+    pkv_status st = check_cfg(cfg);
+    if (st != PKV_OK) return st;
+    if (m < 0 || m > kMaxTokens || n_keys <= 0 || n_keys > kMaxTokens) return PKV_ERR_SHAPE;
+    if (m == 0) return PKV_OK;
+    if (!q || !k_cache || !v_cache || !row_pos || !out) return PKV_ERR_NULL;
+    if (!std::isfinite(softmax_scale) || softmax_scale < 0.f) return PKV_ERR_SHAPE;
+    const size_t need = align256(sparse_row_attn_ws_bytes(*cfg, n_keys, m));
+    if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
+    return launch_sparse_row_attn(*cfg, q, k_cache, v_cache, row_pos, out, lse_out, m,
+                                  n_keys, resolve_scale(softmax_scale, cfg->head_dim),
+                                  ws, (hipStream_t)stream);
+}
+
+size_t pkv_workspace_bytes(int which_call, const pkv_layer_cfg* cfg, int64_t n,
+                           int64_t m) {
+    if (check_cfg(cfg) != PKV_OK || n < 0 || m < 0) return 0;
+    switch (which_call) {
+        case PKV_CALL_QUERY_SCORE:
+            return align256(query_score_ws_bytes(*cfg, n, m));
+        case PKV_CALL_SPARSE_ROW_ATTN:
+            return align256(sparse_row_attn_ws_bytes(*cfg, n, m));
+        default:
+            return 0;
+    }
+}
+
+const char* pkv_status_string(pkv_status status) {
+    switch (status) {
+        case PKV_OK: return "ok";
+        case PKV_ERR_NULL: return "a required pointer is NULL";
+        case PKV_ERR_SHAPE: return "a size argument is negative or inconsistent";
+        case PKV_ERR_UNSUPPORTED: return "dtype, head_dim or head geometry not supported";
+        case PKV_ERR_WORKSPACE: return "workspace missing or too small";
+        case PKV_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+int pkv_version(void) { return 100; }
+
+}  // extern "C"

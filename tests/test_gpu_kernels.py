@@ -1,0 +1,314 @@
+"""GPU parity, call by call: every C-ABI entry point against the CPU oracle on
+the same seeded inputs.  Sizes span several tiles and a ragged tail; edge
+cases (empty, k = 0, k = n, ties, in place, negative and very large positions)
+are included.  Tolerances: index work bit-exact; floating point
+max|a - b| / max|b| <= 1e-4 (fp32 storage) or 2e-2 (bf16 storage), with tighter
+bounds where the arithmetic allows (stated per test)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pkv_oracle as O
+from paper_2602_02579_amd import api, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def dev(x, dtype, device):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if t.dtype in (torch.float32, torch.float64):
+        t = t.to({"f32": torch.float32, "bf16": torch.bfloat16}[dtype])
+    return t.to(device)
+
+
+def host(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def rel_err(got, want):
+    if want.size == 0:
+        return 0.0
+    return float(np.abs(got - want).max() / max(np.abs(want).max(), 1e-30))
+
+
+def rnd(seed, shape, dtype, scale=1.0):
+    x = np.random.default_rng(seed).standard_normal(shape).astype(np.float32) * np.float32(scale)
+    return synth.to_storage(x, dtype)
+
+
+def lcfg(dtype, hq, hkv, d, hid=256, theta=500000.0):
+    return api.LayerCfg(hq, hkv, d, hid, theta, dtype)
+
+
+# ------------------------------------------------------------------ rope
+
+@pytest.mark.parametrize("dtype,n,hkv,d,theta", [
+    ("f32", 1024, 4, 64, 10000.0), ("f32", 333, 2, 32, 10000.0),
+    ("bf16", 8192 + 77, 8, 128, 500000.0), ("bf16", 5, 1, 16, 500000.0),
+    ("bf16", 1000, 3, 256, 500000.0)])
+def test_rope_restore_matches_oracle(gpu_device, dtype, n, hkv, d, theta):
+    cfg = lcfg(dtype, hkv, hkv, d, theta=theta)
+    x = rnd(1, (n, hkv, d), dtype)
+    want = O.rope_restore(x.astype(np.float64), np.arange(n), theta, dtype)
+    k_in = dev(x, dtype, gpu_device)
+    k_out = torch.empty_like(k_in)
+    api.pkv_rope_restore(cfg, k_in, k_out)
+    got = host(k_out)
+    assert rel_err(got, want) <= TOL[dtype]
+    if dtype == "bf16":
+        # same bf16 value almost everywhere, never more than one bf16 step off
+        diff = np.abs(got - want)
+        assert (diff > 0).mean() < 0.02
+        assert (diff <= np.abs(want) * 2.0 ** -7 + 1e-6).all()
+    else:
+        assert np.abs(got - want).max() <= 4e-6
+
+
+def test_rope_restore_positions_inplace_and_inverse(gpu_device):
+    dtype, n, hkv, d, theta = "f32", 700, 2, 64, 500000.0
+    cfg = lcfg(dtype, hkv, hkv, d, theta=theta)
+    x = rnd(2, (n, hkv, d), dtype)
+    pos_np = np.random.default_rng(3).integers(-200000, 200000, size=n).astype(np.int32)
+    pos_np[:4] = [0, 131071, -131071, 1]
+    want = O.rope_restore(x.astype(np.float64), pos_np, theta, dtype)
+    buf = dev(x, dtype, gpu_device)
+    pos = torch.from_numpy(pos_np).to(gpu_device)
+    api.pkv_rope_restore(cfg, buf, buf, pos)          # in place
+    assert np.abs(host(buf) - want).max() <= 4e-6
+    assert np.array_equal(host(buf)[0], x[0].astype(np.float64))   # position 0
+    api.pkv_rope_restore(cfg, buf, buf, -pos)         # inverse rotation
+    assert np.abs(host(buf) - x).max() <= 8e-6
+    # pos_base form equals the explicit form
+    a = dev(x, dtype, gpu_device)
+    b = torch.empty_like(a)
+    c = torch.empty_like(a)
+    api.pkv_rope_restore(cfg, a, b, None, 32768)
+    api.pkv_rope_restore(cfg, a, c, torch.arange(32768, 32768 + n, dtype=torch.int32,
+                                                 device=gpu_device))
+    assert torch.equal(b, c)
+
+
+def test_rope_restore_empty_is_a_noop(gpu_device):
+    cfg = lcfg("bf16", 8, 8, 128)
+    e = torch.empty((0, 8, 128), dtype=torch.bfloat16, device=gpu_device)
+    api.pkv_rope_restore(cfg, e, e)
+
+
+# ------------------------------------------------------------------ scatter
+
+@pytest.mark.parametrize("dtype,hkv,d", [("f32", 4, 64), ("bf16", 8, 128)])
+def test_scatter_kv_is_bit_exact(gpu_device, dtype, hkv, d):
+    cfg = lcfg(dtype, hkv, hkv, d)
+    n_cache, m = 3001, 777
+    g = np.random.default_rng(4)
+    kc, vc = rnd(5, (n_cache, hkv, d), dtype), rnd(6, (n_cache, hkv, d), dtype)
+    kn, vn = rnd(7, (m, hkv, d), dtype), rnd(8, (m, hkv, d), dtype)
+    dst = np.sort(g.choice(n_cache, m, replace=False)).astype(np.int32)
+    dst[-1] = n_cache - 1
+    dst = np.unique(dst).astype(np.int32)
+    m = dst.shape[0]
+    kn, vn = kn[:m], vn[:m]
+    wk, wv = O.scatter_kv(kc, vc, kn, vn, dst)
+    tk, tv = dev(kc, dtype, gpu_device), dev(vc, dtype, gpu_device)
+    api.pkv_scatter_kv(cfg, dev(kn, dtype, gpu_device), dev(vn, dtype, gpu_device),
+                       torch.from_numpy(dst).to(gpu_device), tk, tv)
+    assert np.array_equal(host(tk), wk) and np.array_equal(host(tv), wv)
+    # gather after scatter returns what was scattered
+    assert np.array_equal(host(tk)[dst], kn.astype(np.float64))
+
+
+# ------------------------------------------------------------------ top-k
+
+def run_topk(score_np, k, device):
+    s = torch.from_numpy(score_np.astype(np.float32)).to(device)
+    out = torch.full((max(k, 1),), -7, dtype=torch.int32, device=device)
+    api.pkv_topk_select(s, k, out)
+    return out[:k].cpu().numpy()
+
+
+@pytest.mark.parametrize("n,k", [(1, 1), (63, 10), (64, 64), (1000, 0), (1000, 1000),
+                                 (1024, 204), (32768, 6553), (131072, 26214),
+                                 (100003, 99999), (65, 1)])
+def test_topk_matches_oracle(gpu_device, n, k):
+    s = np.random.default_rng(n + k).random(n).astype(np.float32) / n
+    assert np.array_equal(run_topk(s, k, gpu_device), O.topk_select(s, k))
+
+
+def test_topk_ties_negative_values_and_zeros(gpu_device):
+    g = np.random.default_rng(9)
+    for n, k in [(5000, 1234), (777, 1), (4096, 4095)]:
+        s = g.integers(0, 7, size=n).astype(np.float32)          # heavy ties
+        assert np.array_equal(run_topk(s, k, gpu_device), O.topk_select(s, k))
+    s = np.ones(3000, np.float32)                                 # all equal
+    assert np.array_equal(run_topk(s, 700, gpu_device), np.arange(700))
+    s = g.standard_normal(2000).astype(np.float32)                # signed
+    s[::7] = 0.0
+    s[3::7] = -0.0
+    assert np.array_equal(run_topk(s, 900, gpu_device), O.topk_select(s, 900))
+    assert np.array_equal(run_topk(s, 1500, gpu_device), O.topk_select(s, 1500))
+
+
+# ------------------------------------------------------------------ score
+
+@pytest.mark.parametrize("dtype,nq,n_ctx,hq,hkv,d", [
+    ("f32", 16, 1024, 4, 4, 64), ("f32", 3, 301, 4, 2, 32),
+    ("bf16", 64, 2048 + 37, 32, 8, 128), ("bf16", 5, 100, 8, 8, 64),
+    ("bf16", 7, 515, 10, 2, 128)])
+def test_query_score_matches_oracle(gpu_device, dtype, nq, n_ctx, hq, hkv, d):
+    cfg = lcfg(dtype, hq, hkv, d)
+    q = rnd(10, (nq, hq, d), dtype, 1.3)
+    k = rnd(11, (n_ctx, hkv, d), dtype)
+    want = O.query_score(q.astype(np.float64), k.astype(np.float64))
+    score = torch.full((n_ctx,), 9.0, dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, cfg, n_ctx, nq), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    tq, tk = dev(q, dtype, gpu_device), dev(k, dtype, gpu_device)
+    api.pkv_query_score(cfg, tq, tk, score, accumulate=False, ws=ws)
+    got = host(score)
+    # fp32 arithmetic on identical stored inputs: far inside the paper-level bar
+    assert rel_err(got, want) <= 1e-4
+    assert abs(got.sum() - 1.0) < 1e-4
+    # layer fusion: adding the same layer again doubles the score
+    api.pkv_query_score(cfg, tq, tk, score, accumulate=True, ws=ws)
+    want2 = O.fuse_score(O.fuse_score(np.zeros(n_ctx), want), want)
+    assert rel_err(host(score), want2) <= 1e-4
+    # deterministic
+    s2 = torch.empty_like(score)
+    s3 = torch.empty_like(score)
+    api.pkv_query_score(cfg, tq, tk, s2, ws=ws)
+    api.pkv_query_score(cfg, tq, tk, s3, ws=ws)
+    assert torch.equal(s2, s3)
+
+
+def test_query_score_custom_scale(gpu_device):
+    cfg = lcfg("f32", 2, 2, 32)
+    q, k = rnd(12, (4, 2, 32), "f32"), rnd(13, (200, 2, 32), "f32")
+    want = O.query_score(q.astype(np.float64), k.astype(np.float64), scale=0.05)
+    score = torch.empty(200, dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(4096, dtype=torch.uint8, device=gpu_device)
+    api.pkv_query_score(cfg, dev(q, "f32", gpu_device), dev(k, "f32", gpu_device), score,
+                        softmax_scale=0.05, ws=ws)
+    assert rel_err(host(score), want) <= 1e-4
+
+
+# ------------------------------------------------------------------ projection
+
+@pytest.mark.parametrize("dtype,m,hq,hkv,d,hid,theta", [
+    ("f32", 220, 4, 4, 64, 256, 10000.0), ("f32", 37, 4, 2, 32, 64, 10000.0),
+    ("bf16", 300, 32, 8, 128, 1024, 500000.0), ("bf16", 65, 4, 4, 64, 128, 500000.0),
+    ("bf16", 129, 10, 2, 128, 512, 500000.0)])
+def test_gather_qkv_proj_matches_oracle(gpu_device, dtype, m, hq, hkv, d, hid, theta):
+    cfg = lcfg(dtype, hq, hkv, d, hid, theta)
+    n_rows = 2 * m + 11
+    g = np.random.default_rng(14)
+    hidden = rnd(15, (n_rows, hid), dtype)
+    wq = rnd(16, (hq * d, hid), dtype, 1.0 / np.sqrt(hid))
+    wk = rnd(17, (hkv * d, hid), dtype, 1.0 / np.sqrt(hid))
+    wv = rnd(18, (hkv * d, hid), dtype, 1.0 / np.sqrt(hid))
+    rows = np.sort(g.choice(n_rows, m, replace=False)).astype(np.int32)
+    pos = (rows.astype(np.int64) * 57 + 3).astype(np.int32)       # positions != rows
+    wantq, wantk, wantv = O.project_qkv_rows(
+        hidden.astype(np.float64), rows, pos, wq.astype(np.float64),
+        wk.astype(np.float64), wv.astype(np.float64), hq, hkv, d, theta, dtype)
+    dt = cfg.torch_dtype
+    qo = torch.empty((m, hq, d), dtype=dt, device=gpu_device)
+    ko = torch.empty((m, hkv, d), dtype=dt, device=gpu_device)
+    vo = torch.empty((m, hkv, d), dtype=dt, device=gpu_device)
+    args = (dev(hidden, dtype, gpu_device), torch.from_numpy(rows).to(gpu_device),
+            torch.from_numpy(pos).to(gpu_device), dev(wq, dtype, gpu_device),
+            dev(wk, dtype, gpu_device), dev(wv, dtype, gpu_device))
+    api.pkv_gather_qkv_proj(cfg, *args, qo, ko, vo)
+    for got, want in ((qo, wantq), (ko, wantk), (vo, wantv)):
+        assert rel_err(host(got), want) <= TOL[dtype]
+    # Q only / KV only variants write the same bits
+    q2 = torch.empty_like(qo)
+    api.pkv_gather_qkv_proj(cfg, args[0], args[1], args[2], args[3], None, None,
+                            q2, None, None)
+    assert torch.equal(q2, qo)
+    k2, v2 = torch.empty_like(ko), torch.empty_like(vo)
+    api.pkv_gather_qkv_proj(cfg, args[0], args[1], args[2], None, args[4], args[5],
+                            None, k2, v2)
+    assert torch.equal(k2, ko) and torch.equal(v2, vo)
+    # identity gather
+    q3 = torch.empty_like(qo)
+    api.pkv_gather_qkv_proj(cfg, args[0][rows.astype(np.int64)].contiguous(), None,
+                            args[2], args[3], None, None, q3, None, None)
+    assert torch.equal(q3, qo)
+
+
+# ------------------------------------------------------------------ attention
+
+@pytest.mark.parametrize("dtype,m,n_keys,hq,hkv,d", [
+    ("f32", 220, 1040, 4, 4, 64), ("f32", 19, 130, 4, 2, 32),
+    ("bf16", 333, 2048 + 61, 32, 8, 128), ("bf16", 70, 300, 4, 4, 64),
+    ("bf16", 100, 777, 10, 2, 128), ("bf16", 1, 1, 32, 8, 128)])
+def test_sparse_row_attn_matches_oracle(gpu_device, dtype, m, n_keys, hq, hkv, d):
+    cfg = lcfg(dtype, hq, hkv, d)
+    g = np.random.default_rng(19)
+    q = rnd(20, (m, hq, d), dtype, 1.2)
+    kc, vc = rnd(21, (n_keys, hkv, d), dtype), rnd(22, (n_keys, hkv, d), dtype)
+    pos = np.sort(g.choice(n_keys, m, replace=n_keys < m)).astype(np.int32)
+    pos[0] = 0
+    pos[-1] = n_keys - 1
+    want, want_lse = O.sparse_row_attn(q.astype(np.float64), kc.astype(np.float64),
+                                       vc.astype(np.float64), pos, dtype=dtype)
+    dt = cfg.torch_dtype
+    out = torch.empty((m, hq, d), dtype=dt, device=gpu_device)
+    lse = torch.empty((m, hq), dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, m), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    args = (dev(q, dtype, gpu_device), dev(kc, dtype, gpu_device), dev(vc, dtype, gpu_device))
+    api.pkv_sparse_row_attn(cfg, *args, torch.from_numpy(pos).to(gpu_device), out, lse, ws=ws)
+    assert rel_err(host(out), want) <= TOL[dtype]
+    assert np.abs(host(lse) - want_lse).max() <= 1e-3
+    # row order does not matter: a shuffled row set gives the same rows
+    perm = g.permutation(m)
+    out2 = torch.empty_like(out)
+    api.pkv_sparse_row_attn(cfg, args[0][perm].contiguous(), args[1], args[2],
+                            torch.from_numpy(pos[perm]).to(gpu_device), out2, None, ws=ws)
+    assert rel_err(host(out2), want[perm]) <= TOL[dtype]
+
+
+def test_sparse_row_attn_closed_forms(gpu_device):
+    dtype, hq, hkv, d, n_keys = "bf16", 8, 2, 128, 500
+    cfg = lcfg(dtype, hq, hkv, d)
+    q = rnd(23, (3, hq, d), dtype)
+    kc = rnd(24, (n_keys, hkv, d), dtype)
+    vc = np.broadcast_to(rnd(25, (1, hkv, d), dtype), (n_keys, hkv, d)).copy()
+    out = torch.empty((3, hq, d), dtype=torch.bfloat16, device=gpu_device)
+    pos = torch.tensor([0, 250, 499], dtype=torch.int32, device=gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, 3), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    api.pkv_sparse_row_attn(cfg, dev(q, dtype, gpu_device), dev(kc, dtype, gpu_device),
+                            dev(vc, dtype, gpu_device), pos, out, None, ws=ws)
+    got = host(out)
+    for h in range(hq):   # constant values come back (up to bf16 rounding of the mean)
+        assert np.abs(got[:, h] - vc[0, h // 4]).max() <= 2e-2 * np.abs(vc[0]).max()
+
+
+# ------------------------------------------------------------------ errors
+
+def test_host_checked_errors(gpu_device):
+    cfg = lcfg("bf16", 32, 8, 128, 4096)
+    k = torch.zeros((4, 8, 128), dtype=torch.bfloat16, device=gpu_device)
+    bad = api.LayerCfg(32, 5, 128, 4096, 5e5, "bf16")
+    with pytest.raises(api.PkvError) as e:
+        api.pkv_rope_restore(bad, k[:, :5].contiguous(), k[:, :5].contiguous())
+    assert e.value.status == 2
+    odd = api.LayerCfg(8, 8, 72, 4096, 5e5, "bf16")
+    x = torch.zeros((4, 8, 72), dtype=torch.bfloat16, device=gpu_device)
+    with pytest.raises(api.PkvError) as e:
+        api.pkv_rope_restore(odd, x, x)
+    assert e.value.status == 3
+    s = torch.zeros(10, dtype=torch.float32, device=gpu_device)
+    o = torch.zeros(20, dtype=torch.int32, device=gpu_device)
+    with pytest.raises(api.PkvError) as e:
+        api.pkv_topk_select(s, 11, o)
+    assert e.value.status == 2
+    q = torch.zeros((2, 32, 128), dtype=torch.bfloat16, device=gpu_device)
+    with pytest.raises(api.PkvError) as e:
+        api.pkv_query_score(cfg, q, k, s[:4].contiguous(), ws=None)
+    assert e.value.status == 4

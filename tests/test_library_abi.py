@@ -1,0 +1,68 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol
+that include/pkv.h declares; host-only entry points behave."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_02579_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "pkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pkv_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_on_the_symbol_list():
+    assert declared_symbols() == sorted(api.EXPORTED_SYMBOLS)
+    for name in api.EXPORTED_SYMBOLS:
+        assert hasattr(api, name)
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(api.library_path()):
+        pytest.skip("libpkv.so not built (run python -m paper_2602_02579_amd.build)")
+    lib = ctypes.CDLL(api.library_path())
+    for name in declared_symbols():
+        assert getattr(lib, name) is not None
+
+
+def test_host_only_entry_points():
+    if not os.path.exists(api.library_path()):
+        pytest.skip("libpkv.so not built")
+    assert api.pkv_version() >= 100
+    assert api.pkv_status_string(0) == "ok"
+    assert "workspace" in api.pkv_status_string(4)
+    cfg = api.LayerCfg(32, 8, 128, 4096, 5e5, "bf16")
+    assert api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, cfg, 32768, 128) % 256 == 0
+    assert api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, cfg, 32768, 128) > 0
+    assert api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, cfg, 32768, 0) == 0
+    bad = api.LayerCfg(32, 7, 128, 4096, 5e5, "bf16")
+    assert api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, bad, 32768, 128) == 0
+
+
+def test_argument_errors_are_reported_without_a_gpu():
+    """Null pointers and bad sizes are rejected on the host before any launch."""
+    if not os.path.exists(api.library_path()):
+        pytest.skip("libpkv.so not built")
+    lib = api.load_library()
+    c = api.LayerCfg(32, 8, 128, 4096, 5e5, "bf16")._c()
+    assert lib.pkv_rope_restore(ctypes.byref(c), None, None, None, 0, 5, None) == 1
+    assert lib.pkv_rope_restore(ctypes.byref(c), None, None, None, 0, -1, None) == 2
+    assert lib.pkv_rope_restore(ctypes.byref(c), None, None, None, 0, 0, None) == 0
+    assert lib.pkv_rope_restore(None, None, None, None, 0, 5, None) == 1
+    assert lib.pkv_topk_select(None, 10, 11, None, None, 0, None) == 2
+    assert lib.pkv_topk_select(None, 10, 0, None, None, 0, None) == 0
+    assert lib.pkv_topk_select(None, 10, 3, None, None, 0, None) == 1
+    assert lib.pkv_scatter_kv(ctypes.byref(c), None, None, None, None, None, 5, 3, None) == 2
+    assert lib.pkv_sparse_row_attn(ctypes.byref(c), None, None, None, None, None, None,
+                                   0, 10, 0.0, None, 0, None) == 0
+    assert lib.pkv_sparse_row_attn(ctypes.byref(c), None, None, None, None, None, None,
+                                   4, 10, 0.0, None, 0, None) == 1
+    c2 = api.LayerCfg(32, 8, 72, 4096, 5e5, "bf16")._c()
+    assert lib.pkv_rope_restore(ctypes.byref(c2), None, None, None, 0, 5, None) == 3
