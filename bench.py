@@ -1,0 +1,291 @@
+"""Benchmark of the ProphetKV selective-recompute hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic layer of the 32k
+configuration (Llama-3-8B geometry, 64 x 512-token chunks, 128 query tokens,
+r = 0.2): restore RoPE, project the query rows, score, select, project the
+selected + query rows, scatter, attend.  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+                    [--no-cpu-baseline]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2602_02579_amd import api, pipeline, synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+# --------------------------------------------------------------------------
+# workload on the GPU: seeded draws, planted with the library's own calls
+# --------------------------------------------------------------------------
+
+def gpu_callables(cfg, layer, device):
+    """Rotated-query block and rotation for the planting step, computed with
+    the HIP library (the generator itself holds no method arithmetic)."""
+    lc = pipeline.layer_cfg(cfg)
+    dt = lc.torch_dtype
+    hidden = torch.from_numpy(layer["hidden"]).to(dt).to(device)
+    wq = torch.from_numpy(layer["wq"]).to(dt).to(device)
+
+    def project_q(rows):
+        r = torch.from_numpy(np.asarray(rows, dtype=np.int32)).to(device)
+        q = torch.empty((len(rows), cfg.n_q_heads, cfg.head_dim), dtype=dt, device=device)
+        ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, lc, 0, len(rows)),
+                             256), dtype=torch.uint8, device=device)
+        api.pkv_gather_qkv_proj(lc, hidden, r, r, wq, None, None, q, None, None, ws=ws)
+        return q.float().cpu().numpy()
+
+    f32 = api.LayerCfg(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.hidden,
+                       cfg.theta, "f32")
+
+    def rotate(x, pos):
+        t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(device)
+        p = torch.from_numpy(np.asarray(pos, dtype=np.int32)).to(device)
+        o = torch.empty_like(t)
+        api.pkv_rope_restore(f32, t, o, p)
+        return o.cpu().numpy()
+    return project_q, rotate
+
+
+def build_gpu_workload(cfg, device):
+    layers = []
+    for li in range(cfg.n_layers):
+        layer = synth.make_layer(cfg, li)
+        if li < cfg.n_score_layers:
+            pq, rot = gpu_callables(cfg, layer, device)
+            synth.plant(cfg, layer, li, pq, rot)
+        layers.append(pipeline.upload_layer(cfg, layer, device))
+        del layer
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    return layers
+
+
+# --------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands, on a bounded sample
+# --------------------------------------------------------------------------
+
+def cpu_baseline(cfg, row_stride=16):
+    """Times the CPU oracle on the same seeded workload.  Restore, query
+    projection, score and selection run in full; the row-wise steps
+    (projection, scatter, attention) run on every `row_stride`-th recomputed
+    row and are scaled by the row count."""
+    from oracle import pkv_oracle as O          # only this leg touches oracle/
+    from threadpoolctl import threadpool_info
+
+    n, qn = cfg.n_ctx, cfg.n_query
+    k = synth.select_count(cfg.ratio, n)
+    layer = synth.make_layer(cfg, 0)
+    geo = dict(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+               head_dim=cfg.head_dim, theta=cfg.theta)
+
+    def project_q(rows):
+        rows = np.asarray(rows)
+        return O.project_qkv_rows(layer["hidden"], rows, rows, layer["wq"], layer["wk"],
+                                  layer["wv"], dtype=cfg.dtype, **geo)[0]
+
+    synth.plant(cfg, layer, 0, project_q, lambda x, p: O.rope_rotate(x, p, cfg.theta))
+    L = {name: v.astype(np.float64) for name, v in layer.items()}
+    del layer
+    t = {}
+    t0 = time.perf_counter()
+    k_rope = O.rope_restore(L["k_nope"], np.arange(n), cfg.theta, cfg.dtype)
+    t["rope_restore"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    q_rows = np.arange(n, n + qn)
+    q_s = O.project_qkv_rows(L["hidden"], q_rows, q_rows, L["wq"], L["wk"], L["wv"],
+                             dtype=cfg.dtype, **geo)[0]
+    score = O.fuse_score(np.zeros(n), O.query_score(q_s, k_rope))
+    t["query_score"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    sel = O.topk_select(score, k)
+    t["topk_select"] = time.perf_counter() - t0
+    rows = np.concatenate([sel, q_rows])
+    sample = rows[::row_stride]
+    t0 = time.perf_counter()
+    q, k_new, v_new = O.project_qkv_rows(L["hidden"], sample, sample, L["wq"], L["wk"],
+                                         L["wv"], dtype=cfg.dtype, **geo)
+    t["gather_qkv_proj_sample"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    k_cache = np.zeros((n + qn, cfg.n_kv_heads, cfg.head_dim))
+    v_cache = np.zeros_like(k_cache)
+    k_cache[:n] = k_rope
+    v_cache[:n] = L["v"]
+    k_cache, v_cache = O.scatter_kv(k_cache, v_cache, k_new, v_new, sample)
+    t["scatter_kv_sample"] = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    O.sparse_row_attn(q, k_cache, v_cache, sample, dtype=cfg.dtype)
+    t["sparse_row_attn_sample"] = time.perf_counter() - t0
+    scale = len(rows) / len(sample)
+    full = (t["rope_restore"] + t["query_score"] + t["topk_select"] +
+            scale * (t["gather_qkv_proj_sample"] + t["sparse_row_attn_sample"]) +
+            t["scatter_kv_sample"])
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {
+        "value": len(rows) / full, "unit": "tokens/s", "cores": int(threads),
+        "kind": "oracle",
+        "sample": (f"restore, query projection, score, top-k in full; projection and "
+                   f"attention on every {row_stride}th of the {len(rows)} recomputed rows "
+                   f"({len(sample)} rows), scaled by {scale:.1f}; "
+                   f"measured {sum(t.values()):.1f} s of CPU work"),
+        "seconds": {name: round(v, 3) for name, v in t.items()},
+    }
+
+
+# --------------------------------------------------------------------------
+
+def attn_flops(rows_pos: np.ndarray, hq: int, d: int) -> float:
+    """Causal-masked flops of step 5: QK^T and PV over keys 0..pos inclusive."""
+    return 4.0 * hq * d * float((rows_pos.astype(np.int64) + 1).sum())
+
+
+def time_calls(fn, reps):
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(reps):
+        s.record()
+        fn()
+        e.record()
+        e.synchronize()
+        ts.append(s.elapsed_time(e) * 1e-3)
+    return float(np.median(ts))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "run with --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    api.load_library()           # fails loudly if libpkv.so is missing
+    device = torch.device("cuda:0")
+    torch.cuda.set_device(device)
+    cfg = synth.CONFIGS[args.config]
+    if cfg.n_layers > 4:
+        cfg = cfg.with_(n_layers=4)   # bounded memory for the stacked config
+    layers = build_gpu_workload(cfg, device)
+    sr = pipeline.SelectiveRecompute(cfg, device)
+
+    for _ in range(args.warmup):
+        sr.run(layers)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; the dominant kernel (step 5) is
+    # bracketed by events on the launch stream inside it ---------------------
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps * len(layers))]
+    orig_attn = api.pkv_sparse_row_attn
+    counter = [0]
+
+    def timed_attn(*a, **kw):
+        s, e = ev[counter[0]]
+        counter[0] += 1
+        s.record()
+        orig_attn(*a, **kw)
+        e.record()
+    pipeline.api.pkv_sparse_row_attn = timed_attn
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sr.run(layers)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    pipeline.api.pkv_sparse_row_attn = orig_attn
+    t_attn = float(np.mean([s.elapsed_time(e) for s, e in ev])) * 1e-3
+
+    ms_per_step = elapsed / args.steps * 1e3
+    m_rows = sr.m * len(layers)
+    value = m_rows / (elapsed / args.steps)
+    rows_pos = sr.rows.cpu().numpy()
+    flops = attn_flops(rows_pos, cfg.n_q_heads, cfg.head_dim)
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    achieved = flops / t_attn / 1e12
+
+    # ---- per-call breakdown (outside the timed region) ---------------------
+    L = layers[0]
+    elt = 2 if cfg.dtype == "bf16" else 4
+    row_b = cfg.n_kv_heads * cfg.head_dim * elt
+    calls = {
+        "rope_restore": (lambda: sr.restore(L), 2.0 * cfg.n_ctx * row_b, "hbm"),
+        "query_proj+query_score": (lambda: sr.score_layer(L, False),
+                                   2.0 * cfg.n_q_heads * cfg.n_query * cfg.n_ctx * cfg.head_dim,
+                                   "mfma"),
+        "topk_select": (lambda: sr.select(), 4.0 * cfg.n_ctx + 4.0 * sr.k, "hbm"),
+        "gather_qkv_proj": (lambda: api.pkv_gather_qkv_proj(
+            sr.lc, L["hidden"], sr.rows, sr.rows, L["wq"], L["wk"], L["wv"], sr.q,
+            sr.k_new, sr.v_new, ws=sr.ws),
+            2.0 * sr.m * cfg.hidden * (cfg.n_q_heads + 2 * cfg.n_kv_heads) * cfg.head_dim,
+            "mfma"),
+        "scatter_kv": (lambda: api.pkv_scatter_kv(sr.lc, sr.k_new, sr.v_new, sr.rows,
+                                                  L["k_cache"], L["v_cache"]),
+                       4.0 * sr.m * row_b, "hbm"),
+        "sparse_row_attn": (lambda: api.pkv_sparse_row_attn(
+            sr.lc, sr.q, L["k_cache"], L["v_cache"], sr.rows, sr.out, sr.lse, ws=sr.ws),
+            flops, "mfma"),
+    }
+    breakdown = {}
+    for name, (fn, work, bound) in calls.items():
+        t = time_calls(fn, 10)
+        entry = {"us": round(t * 1e6, 1), "bound": bound}
+        if bound == "hbm":
+            entry["GB/s"] = round(work / t / 1e9, 1)
+            entry["frac"] = round(work / t / 1e9 / PEAK_HBM_GBS, 4)
+        else:
+            entry["TFLOP/s"] = round(work / t / 1e12, 2)
+            entry["frac"] = round(work / t / 1e12 / peak, 4)
+        breakdown[name] = entry
+
+    result = {
+        "metric": "recomputed tokens/s (selective-recompute hot path, 32k ctx, r=0.2)",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "n_ctx": cfg.n_ctx, "n_query": cfg.n_query,
+                   "chunks": f"{cfg.n_chunks}x{cfg.chunk_len}", "ratio": cfg.ratio,
+                   "k": sr.k, "rows_recomputed": sr.m, "layers": len(layers),
+                   "n_score_layers": min(cfg.n_score_layers, len(layers)),
+                   "heads": f"{cfg.n_q_heads}/{cfg.n_kv_heads}", "head_dim": cfg.head_dim,
+                   "hidden": cfg.hidden},
+        "context_tokens_per_s": round(cfg.n_ctx * len(layers) / (elapsed / args.steps), 1),
+        "sparse_row_attn_tflops": round(achieved, 2),
+        "roofline": {"kernel": "pkv_sparse_row_attn", "bound": "mfma",
+                     "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(achieved / peak, 4), "traffic": None,
+                     "flops_per_launch": flops, "avg_launch_s": t_attn},
+        "breakdown": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg.with_(n_layers=1, n_score_layers=1))
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

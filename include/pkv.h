@@ -152,7 +152,8 @@ pkv_status pkv_topk_select(const float* score, /* [n] */
  * q_out may be NULL (then only K and V are produced); k_out and v_out may
  * both be NULL (then only Q is produced).  row_idx values must lie in
  * [0, n_hidden_rows) (checked only against negative m / null pointers on
- * the host).  m == 0 is a no-op.
+ * the host).  Scratch: pkv_workspace_bytes(PKV_CALL_GATHER_QKV_PROJ, cfg, 0, m)
+ * bytes (a cos/sin table of the m row positions).  m == 0 is a no-op.
  */
 pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg,
                                const void* hidden,     /* [n_hidden_rows, hidden] */
@@ -164,7 +165,8 @@ pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg,
                                void* q_out,            /* [m, Hq, D]  */
                                void* k_out,            /* [m, Hkv, D] */
                                void* v_out,            /* [m, Hkv, D] */
-                               int64_t m, void* stream);
+                               int64_t m, void* ws, size_t ws_bytes,
+                               void* stream);
 
 /*
  * Step 4b - cache update (paper: Algorithm 1 "Update layer-wise KV cache":

@@ -89,7 +89,7 @@ def load_library() -> ctypes.CDLL:
                                     ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.pkv_topk_select.argtypes = [f32p, i64, i64, i32p, vp, ctypes.c_size_t, vp]
     lib.pkv_gather_qkv_proj.argtypes = [cfgp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp,
-                                        i64, vp]
+                                        i64, vp, ctypes.c_size_t, vp]
     lib.pkv_scatter_kv.argtypes = [cfgp, vp, vp, i32p, vp, vp, i64, i64, vp]
     lib.pkv_sparse_row_attn.argtypes = [cfgp, vp, vp, vp, i32p, vp, f32p, i64, i64,
                                         ctypes.c_float, vp, ctypes.c_size_t, vp]
@@ -197,7 +197,8 @@ def pkv_gather_qkv_proj(cfg: LayerCfg, hidden: torch.Tensor,
                         wq: Optional[torch.Tensor], wk: Optional[torch.Tensor],
                         wv: Optional[torch.Tensor], q_out: Optional[torch.Tensor],
                         k_out: Optional[torch.Tensor],
-                        v_out: Optional[torch.Tensor]) -> None:
+                        v_out: Optional[torch.Tensor],
+                        ws: Optional[torch.Tensor] = None) -> None:
     m = row_pos.shape[0]
     dt = cfg.torch_dtype
     if hidden.dim() != 2 or hidden.shape[1] != cfg.hidden:
@@ -214,12 +215,13 @@ def pkv_gather_qkv_proj(cfg: LayerCfg, hidden: torch.Tensor,
                            (wv, cfg.n_kv_heads, "wv")):
         if t is not None and tuple(t.shape) != (heads * cfg.head_dim, cfg.hidden):
             raise ValueError(f"{name} must be [heads*D, hidden]")
+    wp, wb = _ws(ws)
     c = cfg._c()
     _check("pkv_gather_qkv_proj", load_library().pkv_gather_qkv_proj(
         ctypes.byref(c), _ptr(hidden, dt, "hidden"), _ptr(row_idx, torch.int32, "row_idx"),
         _ptr(row_pos, torch.int32, "row_pos"), _ptr(wq, dt, "wq"), _ptr(wk, dt, "wk"),
         _ptr(wv, dt, "wv"), _ptr(q_out, dt, "q_out"), _ptr(k_out, dt, "k_out"),
-        _ptr(v_out, dt, "v_out"), m, _stream()))
+        _ptr(v_out, dt, "v_out"), m, wp, wb, _stream()))
 
 
 def pkv_scatter_kv(cfg: LayerCfg, k_new: torch.Tensor, v_new: torch.Tensor,

@@ -76,17 +76,216 @@ __global__ __launch_bounds__(256) void qkv_proj_generic(
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// MFMA kernel: bf16 storage, head_dim 64 or 128, hidden a multiple of 32.
+//
+// C[256 rows x 128 cols] per workgroup, contraction in steps of 32 through
+// double-buffered LDS, v_mfma_f32_32x32x16_bf16.  Both operands have the
+// contraction dimension contiguous in memory (x rows and weight rows), which
+// is exactly what the A and B operands want (8 consecutive k per lane).
+// The gather costs nothing extra: the A-tile loader reads row row_idx[i].
+//
+// The 4 waves sit 2 x 2 over the tile; a wave owns 128 rows and two 32-column
+// blocks chosen so that block 1 is the rotary partner (i + D/2) of block 0.
+// The accumulator of a lane then holds both elements of every rotary pair and
+// the rotation happens in registers, with cos/sin read from a small table
+// [m, D/2] that a pre-pass fills (one sincos per (row, i) for all heads).
+// ---------------------------------------------------------------------------
+
+constexpr int kGM = 256, kGN = 128, kGK = 32;
+constexpr int kAStride = kGK + 8;  // bf16 elements per LDS row (80 bytes)
+
+__global__ void rope_table_kernel(const int32_t* __restrict__ row_pos, int m, int half,
+                                  RopeTable tab, float2* __restrict__ cs) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)m * half) return;
+    const int r = (int)(idx / half), i = (int)(idx % half);
+    float sn, c;
+    rope_sincos((double)row_pos[r], tab.inv_freq[i], &sn, &c);
+    cs[idx] = make_float2(c, sn);
+}
+
+struct ProjParams {
+    const bf16_t* hidden;
+    const int32_t* row_idx;
+    const bf16_t* w[3];   // wq, wk, wv
+    bf16_t* out[3];       // q_out, k_out, v_out (may be null)
+    const float2* cs;     // [m, D/2] (cos, sin)
+    int m, hid, hq, hkv;
+    int tile_begin[4];    // first column tile of Q, K, V, end
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void qkv_proj_mfma(ProjParams p) {
+    __shared__ __align__(16) bf16_t a_lds[2][kGM * kAStride];
+    __shared__ __align__(16) bf16_t b_lds[2][kGN * kAStride];
+    constexpr int HALF = D / 2;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int hh = lane >> 5, l32 = lane & 31;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // which matrix and which 128 output columns
+    const int ct = blockIdx.x;
+    int mat = 0;
+    if (ct >= p.tile_begin[1]) mat = 1;
+    if (ct >= p.tile_begin[2]) mat = 2;
+    const int col0 = (ct - p.tile_begin[mat]) * kGN;   // first output feature of the tile
+    const bf16_t* w = p.w[mat];
+    bf16_t* out = p.out[mat];
+    const int heads_out = mat == 0 ? p.hq : p.hkv;
+    const int row0 = blockIdx.y * kGM;
+
+    // ---- loaders: A 256 x 32 (4 chunks / thread), B 128 x 32 (2 chunks / thread)
+    const bf16_t* a_src[4];
+    int a_dst[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = tid + 256 * i;
+        const int r = c >> 2, kch = c & 3;
+        int gr = row0 + r;
+        if (gr >= p.m) gr = p.m - 1;
+        const int64_t src_row = p.row_idx ? p.row_idx[gr] : gr;
+        a_src[i] = p.hidden + src_row * p.hid + kch * 8;
+        a_dst[i] = r * kAStride + kch * 8;
+    }
+    const bf16_t* b_src[2];
+    int b_dst[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = tid + 256 * i;
+        const int r = c >> 2, kch = c & 3;
+        b_src[i] = w + (int64_t)(col0 + r) * p.hid + kch * 8;
+        b_dst[i] = r * kAStride + kch * 8;
+    }
+    uint4 sa[4], sb[2];
+    auto load_stage = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sa[i] = *reinterpret_cast<const uint4*>(a_src[i] + k0);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) sb[i] = *reinterpret_cast<const uint4*>(b_src[i] + k0);
+    };
+    auto store_stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(&a_lds[buf][a_dst[i]]) = sa[i];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4*>(&b_lds[buf][b_dst[i]]) = sb[i];
+    };
+
+    // wave's column blocks: block 1 is the rotary partner of block 0
+    // D = 128: the tile is one head; wave wn owns i in [32 wn, 32 wn + 32) and i + 64
+    // D = 64 : the tile is two heads; wave wn owns head wn, i in [0, 32) and i + 32
+    const int cb0 = D == 128 ? wn * 32 : wn * 64;
+    const int cb1 = cb0 + HALF;
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+
+    const int n_k = p.hid / kGK;
+    load_stage(0);
+    store_stage(0);
+    __syncthreads();
+    for (int kt = 0; kt < n_k; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < n_k) load_stage((kt + 1) * kGK);
+        const bf16_t* ap = &a_lds[buf][(wm * 128 + l32) * kAStride + hh * 8];
+        const bf16_t* bp = &b_lds[buf][l32 * kAStride + hh * 8];
+#pragma unroll
+        for (int ks = 0; ks < kGK / 16; ++ks) {
+            bf16x8 a[4], b[2];
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+                a[mb] = *reinterpret_cast<const bf16x8*>(ap + mb * 32 * kAStride + ks * 16);
+            b[0] = *reinterpret_cast<const bf16x8*>(bp + cb0 * kAStride + ks * 16);
+            b[1] = *reinterpret_cast<const bf16x8*>(bp + cb1 * kAStride + ks * 16);
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+                acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], b[0], acc[mb][0], 0, 0, 0);
+                acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], b[1], acc[mb][1], 0, 0, 0);
+            }
+        }
+        if (kt + 1 < n_k) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: rotate pairs in registers, round once, store -----------------
+    if (out == nullptr) return;
+    const int head = (col0 + cb0) / D;            // output head of this wave's columns
+    const int i = (col0 + cb0) % D + l32;         // pair index in [0, D/2)
+    const bool rotate = mat != 2;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + wm * 128 + mb * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
+            if (row >= p.m) continue;
+            float a = acc[mb][0][r], b = acc[mb][1][r];
+            if (rotate) {
+                const float2 t = p.cs[(int64_t)row * HALF + i];
+                const float ra = a * t.x - b * t.y;
+                const float rb = b * t.x + a * t.y;
+                a = ra;
+                b = rb;
+            }
+            bf16_t* o = out + ((int64_t)row * heads_out + head) * D + i;
+            o[0] = (bf16_t)a;
+            o[HALF] = (bf16_t)b;
+        }
+}
+
+bool mfma_proj_supported(const pkv_layer_cfg& cfg) {
+    if (cfg.dtype != PKV_BF16 || cfg.hidden % kGK) return false;
+    if (cfg.head_dim == 128) return true;
+    return cfg.head_dim == 64 && cfg.n_q_heads % 2 == 0 && cfg.n_kv_heads % 2 == 0;
+}
+
 }  // namespace
+
+size_t gather_qkv_proj_ws_bytes(const pkv_layer_cfg& cfg, int64_t m) {
+    if (!mfma_proj_supported(cfg)) return 0;
+    return (size_t)m * (cfg.head_dim / 2) * sizeof(float2);
+}
 
 pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
                                   const int32_t* row_idx, const int32_t* row_pos,
                                   const void* wq, const void* wk, const void* wv,
                                   void* q_out, void* k_out, void* v_out,
-                                  int64_t m, hipStream_t st) {
+                                  int64_t m, void* ws, hipStream_t st) {
     if (m == 0) return PKV_OK;
     RopeTable tab;
     fill_rope_table(&tab, cfg.head_dim, (double)cfg.rope_theta);
     const int hq = cfg.n_q_heads, hkv = cfg.n_kv_heads;
+    if (mfma_proj_supported(cfg)) {
+        const int d = cfg.head_dim, half = d / 2;
+        float2* cs = (float2*)ws;
+        const int64_t n_tab = m * half;
+        hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)ceil_div(n_tab, 256)), dim3(256),
+                           0, st, row_pos, (int)m, half, tab, cs);
+        ProjParams p = {};
+        p.hidden = (const bf16_t*)hidden;
+        p.row_idx = row_idx;
+        p.w[0] = (const bf16_t*)wq; p.w[1] = (const bf16_t*)wk; p.w[2] = (const bf16_t*)wv;
+        p.out[0] = (bf16_t*)q_out; p.out[1] = (bf16_t*)k_out; p.out[2] = (bf16_t*)v_out;
+        p.cs = cs;
+        p.m = (int)m; p.hid = cfg.hidden; p.hq = hq; p.hkv = hkv;
+        // column tiles: only the matrices whose outputs were asked for
+        const int tq = q_out ? hq * d / kGN : 0;
+        const int tkv = k_out ? hkv * d / kGN : 0;
+        p.tile_begin[0] = 0;
+        p.tile_begin[1] = tq;
+        p.tile_begin[2] = tq + tkv;
+        p.tile_begin[3] = tq + 2 * tkv;
+        const dim3 grid((unsigned)p.tile_begin[3], (unsigned)ceil_div(m, kGM));
+        if (d == 128) hipLaunchKernelGGL(qkv_proj_mfma<128>, grid, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL(qkv_proj_mfma<64>, grid, dim3(256), 0, st, p);
+        return launch_status();
+    }
     const dim3 grid((unsigned)ceil_div(m, 16), (unsigned)(hq + 2 * hkv));
     if (cfg.dtype == PKV_BF16) {
         hipLaunchKernelGGL(qkv_proj_generic<bf16_t>, grid, dim3(256), 0, st,

@@ -76,7 +76,7 @@ pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg, const void* hidden,
                                const int32_t* row_idx, const int32_t* row_pos,
                                const void* wq, const void* wk, const void* wv,
                                void* q_out, void* k_out, void* v_out, int64_t m,
-                               void* stream) {
+                               void* ws, size_t ws_bytes, void* stream) {
     pkv_status st = check_cfg(cfg);
     if (st != PKV_OK) return st;
     if (m < 0 || m > kMaxTokens) return PKV_ERR_SHAPE;
@@ -86,8 +86,10 @@ pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg, const void* hidden,
     if (!q_out && !k_out) return PKV_ERR_NULL;
     if (q_out && !wq) return PKV_ERR_NULL;
     if (k_out && (!wk || !wv)) return PKV_ERR_NULL;
+    const size_t need = align256(gather_qkv_proj_ws_bytes(*cfg, m));
+    if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
     return launch_gather_qkv_proj(*cfg, hidden, row_idx, row_pos, wq, wk, wv, q_out,
-                                  k_out, v_out, m, (hipStream_t)stream);
+                                  k_out, v_out, m, ws, (hipStream_t)stream);
 }
 
 pkv_status pkv_scatter_kv(const pkv_layer_cfg* cfg, const void* k_new,
@@ -126,6 +128,8 @@ size_t pkv_workspace_bytes(int which_call, const pkv_layer_cfg* cfg, int64_t n,
     switch (which_call) {
         case PKV_CALL_QUERY_SCORE:
             return align256(query_score_ws_bytes(*cfg, n, m));
+        case PKV_CALL_GATHER_QKV_PROJ:
+            return align256(gather_qkv_proj_ws_bytes(*cfg, m));
         case PKV_CALL_SPARSE_ROW_ATTN:
             return align256(sparse_row_attn_ws_bytes(*cfg, n, m));
         default:

@@ -110,11 +110,164 @@ __global__ __launch_bounds__(256) void score_colsum_generic(
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// MFMA path: bf16 storage, head_dim 64 or 128, group size <= 16.
+//
+// Pass 1 reuses the attention kernel of step 5 with its PV half switched off:
+// it yields per-column (max, sum) partials over splits of the key range, which
+// merge_lse_kernel folds into one log2-domain normaliser per column.
+//
+// Pass 2 (below): a workgroup owns 256 keys of one kv head (64 per wave, held
+// in registers as MFMA A operands for the whole kernel) and walks over all
+// columns (query token, head of the group) in blocks of 32:
+//     S^T [64 keys x 32 cols] = K (A, registers) x Q^T (B, from L1/L2)
+//     acc[key] += exp2(S^T * c - lse2[col])
+// The accumulator of lane l holds column l%32, so the running per-key sums
+// stay in registers and are reduced across the 32 lanes once, at the end.
+// Each (kv head, key) partial is written exactly once; finish_score_kernel adds
+// the kv heads in a fixed order, so the score is deterministic.
+// ---------------------------------------------------------------------------
+
+__global__ void merge_lse_kernel(const float* __restrict__ part_ml,
+                                 float* __restrict__ lse2, int ncol, int n_splits,
+                                 float scale_log2) {
+    const int col = blockIdx.x * blockDim.x + threadIdx.x;
+    if (col >= ncol) return;
+    float mx = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, part_ml[((int64_t)s * ncol + col) * 2]);
+    float sum = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+        const float m = part_ml[((int64_t)s * ncol + col) * 2];
+        const float l = part_ml[((int64_t)s * ncol + col) * 2 + 1];
+        if (m != -INFINITY) sum += l * exp2f((m - mx) * scale_log2);
+    }
+    lse2[col] = mx * scale_log2 + log2f(sum);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void score_colsum_mfma(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+    const float* __restrict__ lse2, float* __restrict__ part_score, int nq, int n_ctx,
+    int hq, int hkv, int group, float scale_log2) {
+    constexpr int KC = D / 16;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int hh = lane >> 5, l32 = lane & 31;
+    const int g = blockIdx.y;
+    const int key0 = blockIdx.x * 256 + wave * 64;
+
+    bf16x8 a[2][KC];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        const int key = min(key0 + 32 * kb + l32, n_ctx - 1);
+        const bf16_t* kp = k + ((int64_t)key * hkv + g) * D + hh * 8;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc)
+            a[kb][kc] = *reinterpret_cast<const bf16x8*>(kp + kc * 16);
+    }
+    f32x16 acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[kb][r] = 0.f;
+
+    const int ncol_g = nq * group;
+    for (int c0 = 0; c0 < ncol_g; c0 += 32) {
+        const int col = c0 + l32;
+        const bool valid = col < ncol_g;
+        const int qi = valid ? col / group : 0;
+        const int h = g * group + (valid ? col % group : 0);
+        const bf16_t* qp = q + ((int64_t)qi * hq + h) * D + hh * 8;
+        const float norm = valid ? lse2[(int64_t)qi * hq + h] : INFINITY;
+        f32x16 s[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const bf16x8 b = *reinterpret_cast<const bf16x8*>(qp + kc * 16);
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][kc], b, s[0], 0, 0, 0);
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][kc], b, s[1], 0, 0, 0);
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[kb][r] += exp2f(s[kb][r] * scale_log2 - norm);
+    }
+    // sum over the 32 columns held by the lanes of each half
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float v = acc[kb][r];
+            for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            acc[kb][r] = v;
+        }
+    if (l32 == 0) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key0 + 32 * kb + 8 * (r / 4) + 4 * hh + (r % 4);
+                if (key < n_ctx) part_score[(int64_t)g * n_ctx + key] = acc[kb][r];
+            }
+    }
+}
+
+__global__ void finish_score_kernel(const float* __restrict__ part_score,
+                                    float* __restrict__ score, int n_ctx, int hkv,
+                                    float inv_ncol, int accumulate) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n_ctx) return;
+    float s = 0.f;
+    for (int g = 0; g < hkv; ++g) s += part_score[(int64_t)g * n_ctx + t];
+    s *= inv_ncol;
+    score[t] = accumulate ? score[t] + s : s;
+}
+
+bool mfma_score_supported(const pkv_layer_cfg& cfg) {
+    const int group = cfg.n_q_heads / cfg.n_kv_heads;
+    return cfg.dtype == PKV_BF16 && (cfg.head_dim == 64 || cfg.head_dim == 128) &&
+           group <= 16;
+}
+
+struct SplitPlan {
+    int n_splits, split_len;
+};
+
+SplitPlan plan_splits(const pkv_layer_cfg& cfg, int64_t n_ctx, int64_t nq) {
+    const int group = cfg.n_q_heads / cfg.n_kv_heads;
+    const int64_t tiles = ceil_div(nq, 256 / group) * cfg.n_kv_heads;
+    int64_t want = ceil_div(1024, tiles);
+    const int64_t max_splits = ceil_div(n_ctx, 256);
+    if (want > max_splits) want = max_splits;
+    if (want < 1) want = 1;
+    int64_t len = ceil_div(ceil_div(n_ctx, want), 64) * 64;
+    SplitPlan sp;
+    sp.split_len = (int)len;
+    sp.n_splits = (int)ceil_div(n_ctx, len);
+    return sp;
+}
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
 }  // namespace
 
+pkv_status launch_attn_lse_partials(const pkv_layer_cfg& cfg, const void* q,
+                                    const void* k, int64_t nq, int64_t n_ctx,
+                                    float scale, int n_splits, int split_len,
+                                    float* part_ml, hipStream_t st);
+
 size_t query_score_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_ctx, int64_t nq) {
-    (void)n_ctx;
-    return (size_t)(nq * cfg.n_q_heads) * sizeof(float);
+    const size_t ncol = (size_t)(nq * cfg.n_q_heads);
+    if (!mfma_score_supported(cfg)) return ncol * sizeof(float);
+    const SplitPlan sp = plan_splits(cfg, n_ctx, nq);
+    return align_up(ncol * sizeof(float)) +
+           align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)) +
+           align_up((size_t)cfg.n_kv_heads * n_ctx * sizeof(float));
 }
 
 pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
@@ -124,6 +277,34 @@ pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
     float* lse = (float*)ws;
     const int ncol = (int)(nq * cfg.n_q_heads);
     const int hq = cfg.n_q_heads, hkv = cfg.n_kv_heads, d = cfg.head_dim;
+    if (mfma_score_supported(cfg)) {
+        const SplitPlan sp = plan_splits(cfg, n_ctx, nq);
+        unsigned char* base = (unsigned char*)ws;
+        float* lse2 = (float*)base;
+        float* part_ml = (float*)(base + align_up((size_t)ncol * sizeof(float)));
+        float* part_score = (float*)((unsigned char*)part_ml +
+                                     align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)));
+        const float scale_log2 = scale * 1.4426950408889634f;
+        pkv_status stt = launch_attn_lse_partials(cfg, q, k, nq, n_ctx, scale, sp.n_splits,
+                                                  sp.split_len, part_ml, st);
+        if (stt != PKV_OK) return stt;
+        hipLaunchKernelGGL(merge_lse_kernel, dim3((unsigned)ceil_div(ncol, 256)), dim3(256),
+                           0, st, part_ml, lse2, ncol, sp.n_splits, scale_log2);
+        const dim3 grid((unsigned)ceil_div(n_ctx, 256), (unsigned)hkv);
+        if (d == 128) {
+            hipLaunchKernelGGL(score_colsum_mfma<128>, grid, dim3(256), 0, st,
+                               (const bf16_t*)q, (const bf16_t*)k, lse2, part_score,
+                               (int)nq, (int)n_ctx, hq, hkv, hq / hkv, scale_log2);
+        } else {
+            hipLaunchKernelGGL(score_colsum_mfma<64>, grid, dim3(256), 0, st,
+                               (const bf16_t*)q, (const bf16_t*)k, lse2, part_score,
+                               (int)nq, (int)n_ctx, hq, hkv, hq / hkv, scale_log2);
+        }
+        hipLaunchKernelGGL(finish_score_kernel, dim3((unsigned)ceil_div(n_ctx, 256)),
+                           dim3(256), 0, st, part_score, score, (int)n_ctx, hkv,
+                           1.0f / (float)ncol, accumulate);
+        return launch_status();
+    }
     const unsigned kb = (unsigned)ceil_div(n_ctx, 256);
     if (cfg.dtype == PKV_BF16) {
         hipLaunchKernelGGL(score_lse_generic<bf16_t>, dim3(ncol), dim3(256), 0, st,

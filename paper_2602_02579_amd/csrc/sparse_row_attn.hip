@@ -89,11 +89,408 @@ __global__ __launch_bounds__(256) void sparse_row_attn_generic(
     if (lse_out && tid == 0) lse_out[(int64_t)i * hq + h] = m + logf(l);
 }
 
+
+// ---------------------------------------------------------------------------
+// MFMA kernel: bf16 storage, head_dim 64 or 128, group size G <= 16.
+//
+// A workgroup (4 waves) owns a tile of BM = 256/G consecutive rows of one kv
+// head g and the G query heads that read it: 256 "columns" (row, head), 64
+// per wave.  It walks the keys 0 .. max position of the tile in steps of 64,
+// staging K [64 keys x D] and V^T [D x 64 keys] tiles through double-buffered
+// LDS.  Everything is computed transposed so that the softmax statistics of a
+// column live in one lane (pair) and the probabilities feed the second MFMA
+// straight from the accumulator registers:
+//     S^T [keys x cols] = K  (A, from LDS)  x  Q^T (B, held in registers)
+//     O^T [D    x cols] = V^T(A, from LDS)  x  P^T (B, the S^T accumulators)
+// With v_mfma_f32_32x32x16_bf16 the accumulator of lane l holds column l%32
+// and rows 8*(r/4) + 4*(l/32) + r%4, r = 0..15, while a B operand wants the 8
+// contraction indices 8*(l/32) .. +7.  Reading K row swap_bits23(i) for A row
+// i makes accumulator register r of lane half hh hold key 16*(r/8) + 8*hh +
+// r%8 of the 32-key block, so registers 0..7 (8..15) are exactly the B operand
+// of the first (second) 16 keys and V^T is read with plain contiguous keys.
+// V^T comes from a transposed copy of the value cache made by a streaming
+// pre-pass into the workspace.
+//
+// The same kernel with PV switched off and the key range split over
+// blockIdx-encoded splits produces the per-column (max, sum) partials that
+// the query-score call needs for its normalisers.
+// ---------------------------------------------------------------------------
+
+constexpr int kBN = 64;         // keys per tile
+constexpr int kAttnThreads = 256;
+
+struct AttnParams {
+    const bf16_t* q;
+    const bf16_t* k;
+    const bf16_t* vt;        // [hkv, D, n_pad], zero beyond n_keys
+    const int32_t* row_pos;  // [m] or nullptr when fixed_limit >= 0
+    bf16_t* out;             // [m, hq, D]
+    float* lse;              // [m, hq] or nullptr
+    float* part_ml;          // [n_splits, m*hq, 2] (max in raw logits, sum) or nullptr
+    int m, n_keys, n_pad, hq, hkv, group, bm, n_tiles, n_splits, split_len;
+    int fixed_limit;         // >= 0: every row sees keys 0..fixed_limit
+    float scale_log2;        // softmax scale * log2(e)
+    float scale;
+};
+
+template <int D>
+struct AttnLds {
+    static constexpr int kStride = D + 8;    // bf16 elements per K row
+    static constexpr int vStride = kBN + 8;  // bf16 elements per V^T row
+    static constexpr int kElems = kBN * kStride;
+    static constexpr int vElems = D * vStride;
+    static constexpr size_t bytes = 2 * (size_t)(kElems + vElems) * sizeof(bf16_t);
+};
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+template <int D, bool kPV>
+__global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
+    typedef AttnLds<D> L;
+    constexpr int KC = D / 16;               // contraction chunks of QK^T
+    constexpr int DB = D / 32;               // 32-row blocks of O^T
+    constexpr int CH = D * kBN / 8 / kAttnThreads;  // 16-byte chunks per thread per tile
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    bf16_t* k_lds = reinterpret_cast<bf16_t*>(smem_raw);            // [2][kElems]
+    bf16_t* v_lds = k_lds + 2 * L::kElems;                          // [2][vElems]
+    __shared__ int s_red[2][kAttnThreads / 64];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int hh = lane >> 5;
+    const int l32 = lane & 31;
+
+    // work item: kv head (fastest, so that a head stays on one XCD when
+    // hkv == 8), key split, row tile (heaviest tiles first)
+    int wg = blockIdx.x;
+    const int g = wg % p.hkv;
+    wg /= p.hkv;
+    const int split = wg % p.n_splits;
+    const int tile = p.n_tiles - 1 - wg / p.n_splits;
+
+    // ---- my two columns ----------------------------------------------------
+    int limit[2], row[2], head[2];
+    bool valid[2];
+    int lmax = -1, lmin = 0x7fffffff;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int col = wave * 64 + cb * 32 + l32;
+        const int rl = col / p.group;
+        row[cb] = tile * p.bm + rl;
+        head[cb] = g * p.group + col % p.group;
+        valid[cb] = rl < p.bm && row[cb] < p.m;
+        limit[cb] = -1;
+        if (valid[cb]) {
+            limit[cb] = p.fixed_limit >= 0 ? p.fixed_limit : p.row_pos[row[cb]];
+            lmax = max(lmax, limit[cb]);
+            lmin = min(lmin, limit[cb]);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        lmax = max(lmax, __shfl_xor(lmax, o, 64));
+        lmin = min(lmin, __shfl_xor(lmin, o, 64));
+    }
+    if (lane == 0) s_red[0][wave] = lmax;
+    __syncthreads();
+    int tile_max = -1;
+#pragma unroll
+    for (int w = 0; w < kAttnThreads / 64; ++w) tile_max = max(tile_max, s_red[0][w]);
+    const int wave_min = lmin;  // smallest limit among this wave's valid columns
+
+    const int key_begin = split * p.split_len;
+    const int key_end = min(min(tile_max + 1, p.n_keys), key_begin + p.split_len);
+
+    // ---- Q as B operands, straight from global memory -------------------------
+    bf16x8 qreg[2][KC];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const bf16_t* qp = p.q + ((int64_t)row[cb] * p.hq + head[cb]) * D + hh * 8;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            if (valid[cb]) {
+                qreg[cb][kc] = *reinterpret_cast<const bf16x8*>(qp + kc * 16);
+            } else {
+                for (int j = 0; j < 8; ++j) qreg[cb][kc][j] = (bf16_t)0.0f;
+            }
+        }
+    }
+
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.f, 0.f};
+    f32x16 o_acc[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o_acc[db][cb][r] = 0.f;
+
+    const int n_iter = key_end > key_begin ? (key_end - key_begin + kBN - 1) / kBN : 0;
+
+    // ---- global -> register -> LDS staging --------------------------------------
+    uint4 stage_k[CH], stage_v[CH];
+    auto load_tile = [&](int t0) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = tid + kAttnThreads * i;
+            const int key = c / (D / 8), dch = c % (D / 8);
+            const int kk = min(t0 + key, p.n_keys - 1);
+            stage_k[i] = *reinterpret_cast<const uint4*>(
+                p.k + ((int64_t)kk * p.hkv + g) * D + dch * 8);
+            if (kPV) {
+                const int d = c / (kBN / 8), kch = c % (kBN / 8);
+                stage_v[i] = *reinterpret_cast<const uint4*>(
+                    p.vt + ((int64_t)g * D + d) * p.n_pad + t0 + kch * 8);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = tid + kAttnThreads * i;
+            const int key = c / (D / 8), dch = c % (D / 8);
+            *reinterpret_cast<uint4*>(k_lds + buf * L::kElems + key * L::kStride + dch * 8) =
+                stage_k[i];
+            if (kPV) {
+                const int d = c / (kBN / 8), kch = c % (kBN / 8);
+                *reinterpret_cast<uint4*>(v_lds + buf * L::vElems + d * L::vStride + kch * 8) =
+                    stage_v[i];
+            }
+        }
+    };
+
+    // A-row i of a 32-key block reads key swap_bits23(i) of that block
+    const int prow = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+
+    if (n_iter > 0) {
+        load_tile(key_begin);
+        store_tile(0);
+    }
+    __syncthreads();
+
+    for (int it = 0; it < n_iter; ++it) {
+        const int t0 = key_begin + it * kBN;
+        const int buf = it & 1;
+        if (it + 1 < n_iter) load_tile(t0 + kBN);
+
+        // ---- S^T = K Q^T ---------------------------------------------------------
+        f32x16 s_acc[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s_acc[kb][cb][r] = 0.f;
+        const bf16_t* kt = k_lds + buf * L::kElems + prow * L::kStride + hh * 8;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(kt + kc * 16);
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(kt + 32 * L::kStride + kc * 16);
+            s_acc[0][0] = mfma32(a0, qreg[0][kc], s_acc[0][0]);
+            s_acc[0][1] = mfma32(a0, qreg[1][kc], s_acc[0][1]);
+            s_acc[1][0] = mfma32(a1, qreg[0][kc], s_acc[1][0]);
+            s_acc[1][1] = mfma32(a1, qreg[1][kc], s_acc[1][1]);
+        }
+
+        // ---- online softmax, one column per lane pair (l, l ^ 32) -----------------
+        const bool need_mask = t0 + kBN - 1 > wave_min;
+        bf16x8 pb[4][2];  // P^T as B operands: [16-key chunk][column block]
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            if (need_mask) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = t0 + 32 * kb + 16 * (r / 8) + 8 * hh + (r % 8);
+                        if (key > limit[cb]) s_acc[kb][cb][r] = -INFINITY;
+                    }
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_acc[kb][cb][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run[cb], mx);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float corr = exp2f((m_run[cb] - m_safe) * p.scale_log2);
+            const float msc = m_safe * p.scale_log2;
+            float rs = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float e = exp2f(s_acc[kb][cb][r] * p.scale_log2 - msc);
+                    rs += e;
+                    s_acc[kb][cb][r] = e;
+                }
+            rs += __shfl_xor(rs, 32, 64);
+            l_run[cb] = l_run[cb] * corr + rs;
+            m_run[cb] = m_new;
+            if (kPV) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o_acc[db][cb][r] *= corr;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int j2 = 0; j2 < 2; ++j2)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            pb[2 * kb + j2][cb][e] = (bf16_t)s_acc[kb][cb][8 * j2 + e];
+            }
+        }
+
+        // ---- O^T += V^T P^T ---------------------------------------------------------
+        if (kPV) {
+            const bf16_t* vtile = v_lds + buf * L::vElems + l32 * L::vStride + hh * 8;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(
+                        vtile + db * 32 * L::vStride + kk * 16);
+                    o_acc[db][0] = mfma32(a, pb[kk][0], o_acc[db][0]);
+                    o_acc[db][1] = mfma32(a, pb[kk][1], o_acc[db][1]);
+                }
+        }
+
+        if (it + 1 < n_iter) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue -----------------------------------------------------------------
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        if (!valid[cb]) continue;
+        const int64_t colg = (int64_t)row[cb] * p.hq + head[cb];
+        if (p.part_ml) {
+            if (hh == 0) {
+                float* dst = p.part_ml + ((int64_t)split * p.m * p.hq + colg) * 2;
+                dst[0] = m_run[cb];
+                dst[1] = l_run[cb];
+            }
+        } else {
+            if (kPV) {
+                const float inv = 1.f / l_run[cb];
+                bf16_t* op = p.out + colg * D + 4 * hh;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        bf16x4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            v[e] = (bf16_t)(o_acc[db][cb][4 * r4 + e] * inv);
+                        *reinterpret_cast<bf16x4*>(op + db * 32 + r4 * 8) = v;
+                    }
+            }
+            if (p.lse && hh == 0)
+                p.lse[colg] = m_run[cb] * p.scale + logf(l_run[cb]);
+        }
+    }
+}
+
+// V [n_keys, hkv, D] -> V^T [hkv, D, n_pad], zero for keys >= n_keys.
+// 64 x 64 tiles through LDS; reads and writes are both 16-byte, coalesced.
+__global__ __launch_bounds__(256) void transpose_v_kernel(
+    const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int n_keys, int n_pad,
+    int hkv, int d) {
+    __shared__ bf16_t tile[64][64 + 2];
+    const int t0 = blockIdx.x * 64;
+    const int c0 = blockIdx.y * 64;  // column in the flattened [hkv * D] axis
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = tid + 256 * i;      // 512 chunks of 8 elements
+        const int t = c / 8, dch = c % 8;
+        bf16x8 val;
+        if (t0 + t < n_keys) {
+            val = *reinterpret_cast<const bf16x8*>(
+                v + (int64_t)(t0 + t) * hkv * d + c0 + dch * 8);
+        } else {
+            for (int j = 0; j < 8; ++j) val[j] = (bf16_t)0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tile[dch * 8 + j][t] = val[j];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = tid + 256 * i;
+        const int dd = c / 8, tch = c % 8;
+        bf16x8 val;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) val[j] = tile[dd][tch * 8 + j];
+        // flattened column c0 + dd = g * D + d  ->  row of V^T
+        *reinterpret_cast<bf16x8*>(vt + (int64_t)(c0 + dd) * n_pad + t0 + tch * 8) = val;
+    }
+}
+
+bool mfma_attn_supported(const pkv_layer_cfg& cfg) {
+    const int group = cfg.n_q_heads / cfg.n_kv_heads;
+    return cfg.dtype == PKV_BF16 && (cfg.head_dim == 64 || cfg.head_dim == 128) &&
+           group <= 16;
+}
+
+int64_t pad64(int64_t n) { return (n + 63) & ~(int64_t)63; }
+
+template <int D, bool kPV>
+pkv_status launch_attn_mfma(const AttnParams& p, hipStream_t st) {
+    static bool configured = false;  // per process; the attribute is per function
+    auto kern = attn_mfma_kernel<D, kPV>;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)AttnLds<D>::bytes) != hipSuccess)
+            return PKV_ERR_LAUNCH;
+        configured = true;
+    }
+    const int64_t grid = (int64_t)p.n_tiles * p.n_splits * p.hkv;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kAttnThreads), AttnLds<D>::bytes,
+                       st, p);
+    return launch_status();
+}
+
 }  // namespace
 
 size_t sparse_row_attn_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m) {
-    (void)cfg; (void)n_keys; (void)m;
-    return 0;
+    (void)m;
+    if (!mfma_attn_supported(cfg)) return 0;
+    return (size_t)cfg.n_kv_heads * cfg.head_dim * pad64(n_keys) * sizeof(bf16_t);
+}
+
+// Per-column (max, sum) partials of softmax(q k^T * scale) over keys
+// 0 .. n_ctx-1, split over the keys; used by the query-score call.
+// part_ml: [n_splits, nq*hq, 2].
+pkv_status launch_attn_lse_partials(const pkv_layer_cfg& cfg, const void* q,
+                                    const void* k, int64_t nq, int64_t n_ctx,
+                                    float scale, int n_splits, int split_len,
+                                    float* part_ml, hipStream_t st) {
+    AttnParams p = {};
+    p.q = (const bf16_t*)q;
+    p.k = (const bf16_t*)k;
+    p.part_ml = part_ml;
+    p.m = (int)nq;
+    p.n_keys = (int)n_ctx;
+    p.n_pad = (int)pad64(n_ctx);
+    p.hq = cfg.n_q_heads;
+    p.hkv = cfg.n_kv_heads;
+    p.group = cfg.n_q_heads / cfg.n_kv_heads;
+    p.bm = 256 / p.group;
+    p.n_tiles = (int)ceil_div(nq, p.bm);
+    p.n_splits = n_splits;
+    p.split_len = split_len;
+    p.fixed_limit = (int)n_ctx - 1;
+    p.scale = scale;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    return cfg.head_dim == 128 ? launch_attn_mfma<128, false>(p, st)
+                               : launch_attn_mfma<64, false>(p, st);
 }
 
 pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
@@ -101,9 +498,39 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
                                   const int32_t* row_pos, void* out,
                                   float* lse_out, int64_t m, int64_t n_keys,
                                   float scale, void* ws, hipStream_t st) {
-    (void)ws; (void)n_keys;
     if (m == 0) return PKV_OK;
     const int d = cfg.head_dim;
+    if (mfma_attn_supported(cfg)) {
+        const int n_pad = (int)pad64(n_keys);
+        bf16_t* vt = (bf16_t*)ws;
+        hipLaunchKernelGGL(transpose_v_kernel,
+                           dim3((unsigned)(n_pad / 64), (unsigned)(cfg.n_kv_heads * d / 64)),
+                           dim3(256), 0, st, (const bf16_t*)v_cache, vt, (int)n_keys, n_pad,
+                           cfg.n_kv_heads, d);
+        if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
+        AttnParams p = {};
+        p.q = (const bf16_t*)q;
+        p.k = (const bf16_t*)k_cache;
+        p.vt = vt;
+        p.row_pos = row_pos;
+        p.out = (bf16_t*)out;
+        p.lse = lse_out;
+        p.m = (int)m;
+        p.n_keys = (int)n_keys;
+        p.n_pad = n_pad;
+        p.hq = cfg.n_q_heads;
+        p.hkv = cfg.n_kv_heads;
+        p.group = cfg.n_q_heads / cfg.n_kv_heads;
+        p.bm = 256 / p.group;
+        p.n_tiles = (int)ceil_div(m, p.bm);
+        p.n_splits = 1;
+        p.split_len = n_pad;
+        p.fixed_limit = -1;
+        p.scale = scale;
+        p.scale_log2 = scale * 1.4426950408889634f;
+        return d == 128 ? launch_attn_mfma<128, true>(p, st)
+                        : launch_attn_mfma<64, true>(p, st);
+    }
     const int block = d <= 64 ? 64 : (d <= 128 ? 128 : 256);
     const dim3 grid((unsigned)m, (unsigned)cfg.n_q_heads);
     if (cfg.dtype == PKV_BF16) {

@@ -67,6 +67,7 @@ class SelectiveRecompute:
         ws_bytes = max(
             api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, self.lc, n, qn),
             api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, self.lc, n + qn, self.m),
+            api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, self.lc, 0, self.m),
             256)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
 
@@ -76,7 +77,7 @@ class SelectiveRecompute:
 
     def score_layer(self, L: Dict[str, torch.Tensor], accumulate: bool) -> None:
         api.pkv_gather_qkv_proj(self.lc, L["hidden"], self.q_rows, self.q_rows,
-                                L["wq"], None, None, self.q_s, None, None)
+                                L["wq"], None, None, self.q_s, None, None, ws=self.ws)
         api.pkv_query_score(self.lc, self.q_s, L["k_cache"][:self.n], self.score,
                             accumulate=accumulate, ws=self.ws)
 
@@ -86,7 +87,7 @@ class SelectiveRecompute:
     # ---- Stage II --------------------------------------------------------
     def recompute_layer(self, L: Dict[str, torch.Tensor]) -> None:
         api.pkv_gather_qkv_proj(self.lc, L["hidden"], self.rows, self.rows, L["wq"],
-                                L["wk"], L["wv"], self.q, self.k_new, self.v_new)
+                                L["wk"], L["wv"], self.q, self.k_new, self.v_new, ws=self.ws)
         api.pkv_scatter_kv(self.lc, self.k_new, self.v_new, self.rows, L["k_cache"],
                            L["v_cache"])
         api.pkv_sparse_row_attn(self.lc, self.q, L["k_cache"], L["v_cache"], self.rows,

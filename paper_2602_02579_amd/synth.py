@@ -168,7 +168,7 @@ def plant(cfg: Config, layer: Dict[str, np.ndarray], layer_index: int,
     token gains a component (three such standard deviations) along the mean
     direction of a sample of context-row queries, taken orthogonal to
     ``u_g``, with its component along ``u_g`` then set to
-    ``-2 sigma / mu`` (low user-query affinity).  The stored, position-free
+    ``-3 sigma / mu`` (low user-query affinity).  The stored, position-free
     key is the inverse rotation of the result, re-rounded to storage.
     Returns the index sets and ``u``.
     """
@@ -206,7 +206,7 @@ def plant(cfg: Config, layer: Dict[str, np.ndarray], layer_index: int,
         def make_salient(kr):
             kr = kr + c_sal[None, :, None] * w[None]
             along = (kr * u[None]).sum(axis=2, keepdims=True)
-            target = (-2.0 * sigma / mu)[None, :, None]
+            target = (-3.0 * sigma / mu)[None, :, None]
             return kr + (target - along) * u[None]
         rewrite(salient, make_salient)
         info["w"] = w

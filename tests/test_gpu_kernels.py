@@ -220,22 +220,24 @@ def test_gather_qkv_proj_matches_oracle(gpu_device, dtype, m, hq, hkv, d, hid, t
     args = (dev(hidden, dtype, gpu_device), torch.from_numpy(rows).to(gpu_device),
             torch.from_numpy(pos).to(gpu_device), dev(wq, dtype, gpu_device),
             dev(wk, dtype, gpu_device), dev(wv, dtype, gpu_device))
-    api.pkv_gather_qkv_proj(cfg, *args, qo, ko, vo)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, cfg, 0, m), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    api.pkv_gather_qkv_proj(cfg, *args, qo, ko, vo, ws=ws)
     for got, want in ((qo, wantq), (ko, wantk), (vo, wantv)):
         assert rel_err(host(got), want) <= TOL[dtype]
     # Q only / KV only variants write the same bits
     q2 = torch.empty_like(qo)
     api.pkv_gather_qkv_proj(cfg, args[0], args[1], args[2], args[3], None, None,
-                            q2, None, None)
+                            q2, None, None, ws=ws)
     assert torch.equal(q2, qo)
     k2, v2 = torch.empty_like(ko), torch.empty_like(vo)
     api.pkv_gather_qkv_proj(cfg, args[0], args[1], args[2], None, args[4], args[5],
-                            None, k2, v2)
+                            None, k2, v2, ws=ws)
     assert torch.equal(k2, ko) and torch.equal(v2, vo)
     # identity gather
     q3 = torch.empty_like(qo)
     api.pkv_gather_qkv_proj(cfg, args[0][rows.astype(np.int64)].contiguous(), None,
-                            args[2], args[3], None, None, q3, None, None)
+                            args[2], args[3], None, None, q3, None, None, ws=ws)
     assert torch.equal(q3, qo)
 
 
