@@ -82,7 +82,7 @@ def build_gpu_workload(cfg, device):
 # CPU baseline: the oracle as it stands, on a bounded sample
 # --------------------------------------------------------------------------
 
-def cpu_baseline(cfg, row_stride=16):
+def cpu_baseline(cfg, row_stride=4):
     """Times the CPU oracle on the same seeded workload.  Restore, query
     projection, score and selection run in full; the row-wise steps
     (projection, scatter, attention) run on every `row_stride`-th recomputed
@@ -177,6 +177,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-call", default=None,
+                    help="run the whole path once, then only this call --reps times and "
+                         "exit (for rocprofv3 counter runs): rope_restore, query_score, "
+                         "topk_select, gather_qkv_proj, scatter_kv, sparse_row_attn")
+    ap.add_argument("--reps", type=int, default=3)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -195,6 +200,27 @@ def main():
     for _ in range(args.warmup):
         sr.run(layers)
     torch.cuda.synchronize()
+
+    if args.profile_call:
+        L0 = layers[0]
+        one = {
+            "rope_restore": lambda: sr.restore(L0),
+            "query_score": lambda: sr.score_layer(L0, False),
+            "topk_select": lambda: sr.select(),
+            "gather_qkv_proj": lambda: api.pkv_gather_qkv_proj(
+                sr.lc, L0["hidden"], sr.rows, sr.rows, L0["wq"], L0["wk"], L0["wv"], sr.q,
+                sr.k_new, sr.v_new, ws=sr.ws),
+            "scatter_kv": lambda: api.pkv_scatter_kv(sr.lc, sr.k_new, sr.v_new, sr.rows,
+                                                     L0["k_cache"], L0["v_cache"]),
+            "sparse_row_attn": lambda: api.pkv_sparse_row_attn(
+                sr.lc, sr.q, L0["k_cache"], L0["v_cache"], sr.rows, sr.out, sr.lse, ws=sr.ws),
+        }[args.profile_call]
+        for _ in range(args.reps):
+            one()
+        torch.cuda.synchronize()
+        print(json.dumps({"profiled_call": args.profile_call, "reps": args.reps,
+                          "workload": cfg.name}))
+        return
 
     # ---- timed region: exactly K steps; the dominant kernel (step 5) is
     # bracketed by events on the launch stream inside it ---------------------

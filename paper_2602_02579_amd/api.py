@@ -67,6 +67,11 @@ _LIB: Optional[ctypes.CDLL] = None
 
 
 def library_path() -> str:
+    """Path of the compiled library; PKV_LIBRARY overrides it (for developers who
+    compare builds), there is still no fallback if the file is missing."""
+    override = os.environ.get("PKV_LIBRARY")
+    if override:
+        return override
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpkv.so")
 
 

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(HERE, "libpkv.so")
 
 SOURCES = ["pkv_api.hip", "rope_restore.hip", "query_score.hip",
            "topk_select.hip", "gather_qkv_proj.hip", "scatter_kv.hip",
-           "sparse_row_attn.hip"]
+           "sparse_row_attn.hip", "sparse_row_attn_dma.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,0 +1,33 @@
+// Declarations shared by the MFMA attention kernels (gfx950, bf16).
+#pragma once
+
+#include "pkv_common.h"
+
+namespace pkv {
+
+constexpr int kBN = 64;           // keys per LDS tile
+constexpr int kAttnThreads = 256; // 4 waves per workgroup
+
+struct AttnParams {
+    const bf16_t* q;
+    const bf16_t* k;
+    const bf16_t* vt;        // [hkv, D, n_pad], zero beyond n_keys
+    const int32_t* row_pos;  // [m] or nullptr when fixed_limit >= 0
+    bf16_t* out;             // [m, hq, D]
+    float* lse;              // [m, hq] or nullptr
+    float* part_ml;          // [n_splits, m*hq, 2] (max in raw logits, sum) or nullptr
+    int m, n_keys, n_pad, hq, hkv, group, bm, n_tiles, n_splits, split_len;
+    int fixed_limit;         // >= 0: every row sees keys 0..fixed_limit
+    float scale_log2;        // softmax scale * log2(e)
+    float scale;
+};
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// head_dim 128 attention proper: software-pipelined, K / V^T tiles brought
+// into LDS by direct global->LDS loads (sparse_row_attn_dma.hip)
+pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st);
+
+}  // namespace pkv

@@ -4,7 +4,7 @@
 // selected tokens; Sec. 5.3, this attention dominates the cost; Eq. 1.)
 //
 //   out[i,h] = sum_{t <= row_pos[i]} softmax_t(q[i,h] . K[t,g(h)] * scale) V[t,g(h)]
-#include "pkv_common.h"
+#include "attn_common.h"
 
 namespace pkv {
 
@@ -113,25 +113,10 @@ __global__ __launch_bounds__(256) void sparse_row_attn_generic(
 //
 // The same kernel with PV switched off and the key range split over
 // blockIdx-encoded splits produces the per-column (max, sum) partials that
-// the query-score call needs for its normalisers.
+// the query-score call needs for its normalisers.  For head_dim 128 the
+// attention proper runs in the software-pipelined kernel of
+// sparse_row_attn_dma.hip; this one serves head_dim 64 and the partials.
 // ---------------------------------------------------------------------------
-
-constexpr int kBN = 64;         // keys per tile
-constexpr int kAttnThreads = 256;
-
-struct AttnParams {
-    const bf16_t* q;
-    const bf16_t* k;
-    const bf16_t* vt;        // [hkv, D, n_pad], zero beyond n_keys
-    const int32_t* row_pos;  // [m] or nullptr when fixed_limit >= 0
-    bf16_t* out;             // [m, hq, D]
-    float* lse;              // [m, hq] or nullptr
-    float* part_ml;          // [n_splits, m*hq, 2] (max in raw logits, sum) or nullptr
-    int m, n_keys, n_pad, hq, hkv, group, bm, n_tiles, n_splits, split_len;
-    int fixed_limit;         // >= 0: every row sees keys 0..fixed_limit
-    float scale_log2;        // softmax scale * log2(e)
-    float scale;
-};
 
 template <int D>
 struct AttnLds {
@@ -141,10 +126,6 @@ struct AttnLds {
     static constexpr int vElems = D * vStride;
     static constexpr size_t bytes = 2 * (size_t)(kElems + vElems) * sizeof(bf16_t);
 };
-
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
 
 template <int D, bool kPV>
 __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
@@ -528,8 +509,7 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         p.fixed_limit = -1;
         p.scale = scale;
         p.scale_log2 = scale * 1.4426950408889634f;
-        return d == 128 ? launch_attn_mfma<128, true>(p, st)
-                        : launch_attn_mfma<64, true>(p, st);
+        return d == 128 ? launch_attn_dma128(p, st) : launch_attn_mfma<64, true>(p, st);
     }
     const int block = d <= 64 ? 64 : (d <= 128 ? 128 : 256);
     const dim3 grid((unsigned)m, (unsigned)cfg.n_q_heads);

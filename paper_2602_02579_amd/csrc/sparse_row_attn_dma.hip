@@ -1,0 +1,410 @@
+// Step 5, head_dim 128, bf16: the attention kernel that the benchmark times.
+// (Paper: Sec. 4.3 Stage II - complete recomputation, but only for the selected
+// tokens; Sec. 5.3 - this attention over the long cache dominates the cost.)
+//
+// Tiling and register layouts are those of attn_mfma_kernel (see
+// sparse_row_attn.hip): a workgroup of 4 waves owns 256 (row, head) columns of
+// one kv head, everything is computed transposed,
+//     S^T = K Q^T,   O^T += V^T P^T     (v_mfma_f32_32x32x16_bf16)
+// and the probabilities go from the S^T accumulators straight into the second
+// MFMA.  What is different here is how the kernel is kept busy:
+//
+// * One wave per SIMD (~450 registers), so MFMA and softmax work overlap only
+//   inside one instruction stream.  On this chip a SIMD issues one VALU-class
+//   instruction per 4 cycles and an MFMA 32x32x16 holds the matrix pipe for 8
+//   such slots, so at most ~7 other instructions per MFMA are free.  The keys
+//   of a 64-key tile are processed as two 32-key sub-steps; in sub-step u
+//       phase A: S^T(u+1) MFMAs   next to   P(u) = exp2(S^T(u) c - ref)   (VALU)
+//       phase B: O^T += V^T P^T(u) MFMAs   next to   mask / max of S^T(u+1)
+//   with sched_group_barrier pinning one MFMA per handful of VALU instructions.
+// * LDS -> register operand loads are issued one phase ahead of their MFMAs.
+// * K and V^T tiles reach LDS by direct global->LDS loads (no staging
+//   registers, no ds_write), 4 stages deep, issued three tiles ahead; the only
+//   synchronisation per 64 keys is one s_waitcnt vmcnt + one barrier.  The
+//   LDS tiles are unpadded; a 16-byte-chunk XOR swizzle (applied on the global
+//   address side of the load) keeps the MFMA operand reads conflict free.
+//   The loads are inline asm because the compiler would otherwise make every
+//   LDS read wait for all outstanding global->LDS loads.
+// * The reference maximum of a column is raised only when a score exceeds it
+//   by 2^40 (see PKV_RESCALE), so the output accumulators never leave the
+//   MFMA-only registers in the hot loop.
+#include "attn_common.h"
+
+namespace pkv {
+
+namespace {
+
+constexpr int D = 128;
+constexpr int KC = D / 16;             // contraction chunks of S^T
+constexpr int DB = D / 32;             // 32-row blocks of O^T
+constexpr int NS = 4;                  // LDS stages per operand
+constexpr int kStageK = kBN * D * 2;   // bytes: 64 keys x 256 B
+constexpr int kStageV = D * kBN * 2;   // bytes: 128 d-rows x 128 B
+constexpr int kLdsBytes = NS * (kStageK + kStageV);
+
+// 16 bytes per lane from global memory straight into LDS: lane i of the wave
+// writes LDS bytes [lds_base + 16 i, +16); lds_base must be wave-uniform.
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t voffset, uint32_t lds_base) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2"
+        :
+        : "s"(lds_base), "v"(voffset), "s"(gbase)
+        : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int s_red[kAttnThreads / 64];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int hh = lane >> 5;
+    const int l32 = lane & 31;
+
+    // kv head fastest: with 8 kv heads a head stays on one XCD and its K/V
+    // stream is shared through that XCD's L2; heaviest row tiles first
+    int wg = blockIdx.x;
+    const int g = wg % p.hkv;
+    wg /= p.hkv;
+    const int tile = p.n_tiles - 1 - wg;
+
+    int limit[2], row[2], head[2];
+    bool valid[2];
+    int lmax = -1, lmin = 0x7fffffff;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int col = wave * 64 + cb * 32 + l32;
+        const int rl = col / p.group;
+        row[cb] = tile * p.bm + rl;
+        head[cb] = g * p.group + col % p.group;
+        valid[cb] = rl < p.bm && row[cb] < p.m;
+        limit[cb] = -1;
+        if (valid[cb]) {
+            limit[cb] = p.row_pos[row[cb]];
+            lmax = max(lmax, limit[cb]);
+            lmin = min(lmin, limit[cb]);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        lmax = max(lmax, __shfl_xor(lmax, o, 64));
+        lmin = min(lmin, __shfl_xor(lmin, o, 64));
+    }
+    if (lane == 0) s_red[wave] = lmax;
+    __syncthreads();
+    int tile_max = -1;
+#pragma unroll
+    for (int w = 0; w < kAttnThreads / 64; ++w) tile_max = max(tile_max, s_red[w]);
+    const int key_end = min(tile_max + 1, p.n_keys);
+    // (wave-uniform values are moved to scalar registers explicitly: they feed
+    // the scalar operands of the global->LDS loads and the loop control)
+    const int n_iter = __builtin_amdgcn_readfirstlane((key_end + kBN - 1) / kBN);
+    if (n_iter <= 0) return;  // block-uniform: the tile has no valid row
+    // sub-steps [0, u_unm) lie entirely at or below every limit of this wave
+    const int u_unm = __builtin_amdgcn_readfirstlane(lmin == 0x7fffffff ? 0 : (lmin + 1) / 32);
+
+    // ---- Q as B operands -----------------------------------------------------------
+    bf16x8 qreg[2][KC];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const bf16_t* qp = p.q + ((int64_t)row[cb] * p.hq + head[cb]) * D + hh * 8;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            if (valid[cb]) {
+                qreg[cb][kc] = *reinterpret_cast<const bf16x8*>(qp + kc * 16);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qreg[cb][kc][e] = (bf16_t)0.0f;
+            }
+        }
+    }
+
+    float m_run[2] = {-INFINITY, -INFINITY};
+    float l_run[2] = {0.f, 0.f};
+    f32x16 o_acc[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o_acc[db][cb][r] = 0.f;
+
+    // ---- global -> LDS loads ---------------------------------------------------------
+    // K stage: row r (key) at byte r*256, logical 16-byte chunk c stored at chunk
+    // c ^ (r & 15).  V^T stage: row d at byte d*128, chunk c at c ^ ((d >> 1) & 7).
+    // A wave instruction fills 1 KB of LDS: 4 K rows or 8 V^T rows; wave w owns
+    // K rows [16w, 16w+16) and V^T rows [32w, 32w+32) of every tile.
+    const uint32_t lds_k = (uint32_t)(uintptr_t)smem;
+    const uint32_t lds_v = lds_k + NS * kStageK;
+    const uint32_t k_row_bytes = (uint32_t)p.hkv * D * 2;
+    uint32_t voff_k[4], voff_v[4];
+    int krow[4], kchunk16[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = 16 * wave + 4 * i + (lane >> 4);
+        krow[i] = r;
+        kchunk16[i] = (((lane & 15) ^ (r & 15)) * 16);
+        voff_k[i] = (uint32_t)r * k_row_bytes + kchunk16[i];
+        const int d = 32 * wave + 8 * i + (lane >> 3);
+        voff_v[i] = (uint32_t)d * (uint32_t)p.n_pad * 2u + (((lane & 7) ^ ((d >> 1) & 7)) * 16);
+    }
+    const uint32_t lds_k_wave = __builtin_amdgcn_readfirstlane(lds_k + wave * 16 * 256);
+    const uint32_t lds_v_wave = __builtin_amdgcn_readfirstlane(lds_v + wave * 32 * 128);
+    const bf16_t* const k_head = p.k + (int64_t)g * D;
+    const bf16_t* const v_head = p.vt + (int64_t)g * D * p.n_pad;
+
+    // K tile t (clamped to the last tile) into stage st
+#define PKV_DMA_K(T, ST)                                                                 \
+    {                                                                                    \
+        const int t_ = min((T), n_iter - 1);                                             \
+        const int t0_ = t_ * kBN;                                                        \
+        const bf16_t* gb_ = k_head + (int64_t)t0_ * p.hkv * D;                           \
+        const uint32_t lb_ = lds_k_wave + (ST) * kStageK;                                \
+        if (t0_ + kBN <= p.n_keys) {                                                     \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                \
+                dma16(gb_, voff_k[i], lb_ + i * 1024);                                   \
+        } else { /* last, ragged tile: rows past the cache re-read its last row */      \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                              \
+                const int r_ = min(krow[i], p.n_keys - 1 - t0_);                         \
+                dma16(gb_, (uint32_t)r_ * k_row_bytes + kchunk16[i], lb_ + i * 1024);    \
+            }                                                                            \
+        }                                                                                \
+    }
+#define PKV_DMA_V(T, ST)                                                                 \
+    {                                                                                    \
+        const int t_ = min((T), n_iter - 1);                                             \
+        const bf16_t* gb_ = v_head + t_ * kBN;                                           \
+        const uint32_t lb_ = lds_v_wave + (ST) * kStageV;                                \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                    \
+            dma16(gb_, voff_v[i], lb_ + i * 1024);                                       \
+    }
+
+    // ---- LDS -> register operand addresses (bytes inside a stage) ------------------------
+    // A-row i of a 32-key block reads key swap_bits23(i) of that block, so that
+    // accumulator register r of lane half hh holds key 16*(r/8) + 8*hh + r%8.
+    const int prow = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+    uint32_t kaddr[KC], vaddr[4];
+    {
+        const uint32_t a0 = prow * 256 + (((prow & 15) ^ hh) * 16);
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) kaddr[kc] = a0 ^ (kc << 5);
+        const uint32_t v0 = l32 * 128 + ((((l32 >> 1) & 7) ^ hh) * 16);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) vaddr[q] = v0 ^ (q << 5);
+    }
+    const float c2 = p.scale_log2;
+
+    f32x16 s_a[2], s_b[2];   // S^T of one 32-key sub-step, per column block
+    bf16x8 ka[KC], va[2][DB];
+
+    // operands of the 32-key half H of the K tile in stage ST
+#define PKV_LOAD_KA(ST, H)                                                               \
+    _Pragma("unroll") for (int kc = 0; kc < KC; ++kc)                                    \
+        ka[kc] = *reinterpret_cast<const bf16x8*>(                                       \
+            smem + (ST) * kStageK + (H) * 32 * 256 + kaddr[kc]);
+    // V^T operands of the 32-key half H of the tile in stage ST
+#define PKV_LOAD_VA(ST, H)                                                               \
+    _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                     \
+    _Pragma("unroll") for (int db = 0; db < DB; ++db)                                    \
+        va[kk][db] = *reinterpret_cast<const bf16x8*>(                                   \
+            smem + NS * kStageK + (ST) * kStageV + db * 32 * 128 + vaddr[2 * (H) + kk]);
+
+    // S^T = K Q^T for the 32 keys whose operands sit in ka
+#define PKV_QK(S)                                                                        \
+    {                                                                                    \
+        const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,                       \
+                           0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};                      \
+        S[0] = mfma32(ka[0], qreg[0][0], z_);                                            \
+        S[1] = mfma32(ka[0], qreg[1][0], z_);                                            \
+        _Pragma("unroll") for (int kc = 1; kc < KC; ++kc) {                              \
+            S[0] = mfma32(ka[kc], qreg[0][kc], S[0]);                                    \
+            S[1] = mfma32(ka[kc], qreg[1][kc], S[1]);                                    \
+        }                                                                                \
+    }
+
+    // mask (optional) and maximum of a score buffer; raises `grow`
+#define PKV_STATS(S, T0, MASK)                                                           \
+    _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) {                                   \
+        if (MASK) {                                                                      \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                             \
+                const int key_ = (T0) + 16 * (r / 8) + 8 * hh + (r % 8);                 \
+                if (key_ > limit[cb]) S[cb][r] = -INFINITY;                              \
+            }                                                                            \
+        }                                                                                \
+        float mx_ = S[cb][0];                                                            \
+        _Pragma("unroll") for (int r = 1; r < 16; ++r) mx_ = fmaxf(mx_, S[cb][r]);       \
+        mx_ = fmaxf(mx_, __shfl_xor(mx_, 32, 64));                                       \
+        m_new[cb] = fmaxf(m_run[cb], mx_);                                               \
+        grow = grow || (mx_ * c2 - msc[cb] > kLazy);                                     \
+    }
+
+    // The reference maximum m_run of a column is NOT the running maximum: it is
+    // raised (and the accumulators rescaled) only when a score exceeds it by more
+    // than kLazy in the exp2 domain.  Probabilities then reach 2^kLazy at most,
+    // far inside the range of bf16/fp32, and relative precision does not depend
+    // on the reference.  The rescale is therefore a cold path, and the output
+    // accumulators can stay in MFMA-only registers throughout the hot loop.
+#define PKV_RESCALE()                                                                    \
+    if (__builtin_expect(__any(grow), 0)) {                                              \
+        _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) {                               \
+            const float ms_ = m_new[cb] == -INFINITY ? 0.f : m_new[cb];                  \
+            const float corr_ = __builtin_amdgcn_exp2f((m_run[cb] - ms_) * c2);          \
+            l_run[cb] *= corr_;                                                          \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db)                            \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) o_acc[db][cb][r] *= corr_;    \
+            m_run[cb] = m_new[cb];                                                       \
+            msc[cb] = ms_ * c2;                                                          \
+        }                                                                                \
+    }
+
+    // one 32-key sub-step u: CUR holds S^T(u); NXT receives S^T(u+1) (operands
+    // already in ka); (KST, KH) name the K half tile of sub-step u+2, (VST, VH)
+    // the V^T half tile of sub-step u.
+#define PKV_SUBSTEP(CUR, NXT, KST, KH, VST, VH, T0_NEXT, MASK)                           \
+    {                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+        PKV_LOAD_VA(VST, VH)                                                             \
+        PKV_QK(NXT)                                                                      \
+        bf16x8 pb_[2][2];                                                                \
+        _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) {                               \
+            float rs_ = 0.f;                                                             \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                             \
+                const float e_ = __builtin_amdgcn_exp2f(CUR[cb][r] * c2 - msc[cb]);      \
+                rs_ += e_;                                                               \
+                pb_[r / 8][cb][r % 8] = (bf16_t)e_;                                      \
+            }                                                                            \
+            rs_ += __shfl_xor(rs_, 32, 64);                                              \
+            l_run[cb] += rs_;                                                            \
+        }                                                                                \
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);                          \
+        _Pragma("unroll") for (int i_ = 0; i_ < 2 * KC; ++i_) {                          \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           \
+            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);                           \
+        }                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+        PKV_LOAD_KA(KST, KH)                                                             \
+        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                 \
+        _Pragma("unroll") for (int db = 0; db < DB; ++db) {                              \
+            o_acc[db][0] = mfma32(va[kk][db], pb_[kk][0], o_acc[db][0]);                 \
+            o_acc[db][1] = mfma32(va[kk][db], pb_[kk][1], o_acc[db][1]);                 \
+        }                                                                                \
+        grow = false;                                                                    \
+        PKV_STATS(NXT, T0_NEXT, MASK)                                                    \
+        __builtin_amdgcn_sched_group_barrier(0x100, KC, 0);                              \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4 * DB; ++i_) {                          \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           \
+            __builtin_amdgcn_sched_group_barrier(0x002, (MASK) ? 8 : 3, 0);              \
+        }                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+    }
+
+    // one 64-key tile J whose V^T sits in stage SV0 and whose successor's K sits in
+    // stage SK1; K(J+3) and V^T(J+2) are requested into SDK / SDV
+#define PKV_TILE(J, SK1, SV0, SDK, SDV, MASK)                                            \
+    {                                                                                    \
+        const int t0_tile_ = (J) * kBN;                                                  \
+        PKV_DMA_K((J) + 3, SDK)                                                          \
+        PKV_DMA_V((J) + 2, SDV)                                                          \
+        PKV_SUBSTEP(s_a, s_b, SK1, 0, SV0, 0, t0_tile_ + 32, MASK)                       \
+        PKV_RESCALE()                                                                    \
+        PKV_SUBSTEP(s_b, s_a, SK1, 1, SV0, 1, t0_tile_ + 64, MASK)                       \
+        wait_vm<8>();   /* K(J+2), V^T(J+1) have landed; 8 newer loads stay in flight */ \
+        __syncthreads();                                                                 \
+        PKV_RESCALE()                                                                    \
+    }
+
+    // ---- prologue ---------------------------------------------------------------------
+    PKV_DMA_K(0, 0)
+    PKV_DMA_V(0, 0)
+    PKV_DMA_K(1, 1)
+    wait_vm<0>();
+    __syncthreads();
+    constexpr float kLazy = 40.f;
+    float m_new[2];
+    float msc[2] = {0.f, 0.f};   // reference maximum times c2 (0 while it is -inf)
+    bool grow = false;
+    PKV_LOAD_KA(0, 0)
+    PKV_QK(s_a)
+    PKV_LOAD_KA(0, 1)            // operands of S^T(1)
+    PKV_STATS(s_a, 0, true)
+    // first sub-step: nothing accumulated yet, the reference is simply its maximum
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        m_run[cb] = m_new[cb];
+        msc[cb] = (m_run[cb] == -INFINITY ? 0.f : m_run[cb]) * c2;
+    }
+    grow = false;
+    PKV_DMA_K(2, 2)
+    PKV_DMA_V(1, 1)
+
+    // ---- main loop: four tiles per trip so that every LDS stage is a constant ------------
+    // tile j is mask free when the statistics it computes (sub-steps 2j+1, 2j+2)
+    // are: 2j + 2 < u_unm
+    int n_unm = min(n_iter, max(0, (u_unm - 1) / 2));
+    n_unm &= ~3;
+    int j = 0;
+    for (; j < n_unm; j += 4) {
+        PKV_TILE(j, 1, 0, 3, 2, false)
+        PKV_TILE(j + 1, 2, 1, 0, 3, false)
+        PKV_TILE(j + 2, 3, 2, 1, 0, false)
+        PKV_TILE(j + 3, 0, 3, 2, 1, false)
+    }
+    for (; j < n_iter; ++j) {
+        PKV_TILE(j, (j + 1) & 3, j & 3, (j + 3) & 3, (j + 2) & 3, true)
+    }
+    wait_vm<0>();   // nothing may still be writing LDS when the workgroup retires
+
+#undef PKV_DMA_K
+#undef PKV_DMA_V
+#undef PKV_LOAD_KA
+#undef PKV_LOAD_VA
+#undef PKV_QK
+#undef PKV_STATS
+#undef PKV_RESCALE
+#undef PKV_SUBSTEP
+#undef PKV_TILE
+
+    // ---- epilogue ----------------------------------------------------------------------
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        if (!valid[cb]) continue;
+        const int64_t colg = (int64_t)row[cb] * p.hq + head[cb];
+        const float inv = 1.f / l_run[cb];
+        bf16_t* op = p.out + colg * D + 4 * hh;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                bf16x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(o_acc[db][cb][4 * r4 + e] * inv);
+                *reinterpret_cast<bf16x4*>(op + db * 32 + r4 * 8) = v;
+            }
+        if (p.lse && hh == 0) p.lse[colg] = m_run[cb] * p.scale + logf(l_run[cb]);
+    }
+}
+
+}  // namespace
+
+pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dma128_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes) != hipSuccess)
+            return PKV_ERR_LAUNCH;
+        configured = true;
+    }
+    const int64_t grid = (int64_t)p.n_tiles * p.hkv;
+    hipLaunchKernelGGL(attn_dma128_kernel, dim3((unsigned)grid), dim3(kAttnThreads),
+                       kLdsBytes, st, p);
+    return launch_status();
+}
+
+}  // namespace pkv
