@@ -180,7 +180,8 @@ def main():
     ap.add_argument("--profile-call", default=None,
                     help="run the whole path once, then only this call --reps times and "
                          "exit (for rocprofv3 counter runs): rope_restore, query_score, "
-                         "topk_select, gather_qkv_proj, scatter_kv, sparse_row_attn")
+                         "topk_select, gather_qkv_proj, scatter_kv, sparse_row_attn; or "
+                         "copy = a plain 1 GiB device copy that calibrates the HBM counters")
     ap.add_argument("--reps", type=int, default=3)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -203,7 +204,10 @@ def main():
 
     if args.profile_call:
         L0 = layers[0]
+        cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=device)
+        cal_dst = torch.empty_like(cal_src)
         one = {
+            "copy": lambda: cal_dst.copy_(cal_src),
             "rope_restore": lambda: sr.restore(L0),
             "query_score": lambda: sr.score_layer(L0, False),
             "topk_select": lambda: sr.select(),

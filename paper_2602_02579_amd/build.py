@@ -19,12 +19,13 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libpkv.so")
 
 SOURCES = ["pkv_api.hip", "rope_restore.hip", "query_score.hip",
-           "topk_select.hip", "gather_qkv_proj.hip", "scatter_kv.hip",
+           "topk_select.hip", "gather_qkv_proj.hip", "gather_qkv_proj_dma.hip",
+           "scatter_kv.hip",
            "sparse_row_attn.hip", "sparse_row_attn_dma.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument",
+         "-Wno-unused-command-line-argument", "-Wno-inline-asm",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

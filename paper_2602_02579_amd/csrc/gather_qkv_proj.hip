@@ -7,7 +7,7 @@
 // out[i, head, :] = R(row_pos[i]) (W_head x_i),  x_i = hidden[row_idx[i]]
 // for the Hq query heads, the Hkv key heads, and (without R) the Hkv value
 // heads; fp32 accumulation; one rounding after the rotation.
-#include "pkv_common.h"
+#include "proj_common.h"
 
 namespace pkv {
 
@@ -105,16 +105,6 @@ __global__ void rope_table_kernel(const int32_t* __restrict__ row_pos, int m, in
     rope_sincos((double)row_pos[r], tab.inv_freq[i], &sn, &c);
     cs[idx] = make_float2(c, sn);
 }
-
-struct ProjParams {
-    const bf16_t* hidden;
-    const int32_t* row_idx;
-    const bf16_t* w[3];   // wq, wk, wv
-    bf16_t* out[3];       // q_out, k_out, v_out (may be null)
-    const float2* cs;     // [m, D/2] (cos, sin)
-    int m, hid, hq, hkv;
-    int tile_begin[4];    // first column tile of Q, K, V, end
-};
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void qkv_proj_mfma(ProjParams p) {
@@ -274,6 +264,15 @@ pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
         p.out[0] = (bf16_t*)q_out; p.out[1] = (bf16_t*)k_out; p.out[2] = (bf16_t*)v_out;
         p.cs = cs;
         p.m = (int)m; p.hid = cfg.hidden; p.hq = hq; p.hkv = hkv;
+        if (proj_dma128_supported(cfg, m)) {
+            const int tq = q_out ? hq * d / kProjDmaTile : 0;
+            const int tkv = k_out ? hkv * d / kProjDmaTile : 0;
+            p.tile_begin[0] = 0;
+            p.tile_begin[1] = tq;
+            p.tile_begin[2] = tq + tkv;
+            p.tile_begin[3] = tq + 2 * tkv;
+            return launch_proj_dma128(p, st);
+        }
         // column tiles: only the matrices whose outputs were asked for
         const int tq = q_out ? hq * d / kGN : 0;
         const int tkv = k_out ? hkv * d / kGN : 0;

@@ -1,0 +1,280 @@
+// Step 4a on the matrix cores, head_dim 128, bf16: the gathered projection
+// C^T[features, tokens] = W . X^T with the rotation of Q and K fused into the
+// store.  (Paper: Algorithm 1, "Recompute KV cache at layer l" / "Calculate
+// user query KV cache"; Appendix E: only the selected rows go through the
+// projection.)
+//
+// One workgroup (4 waves, 2 x 2) owns 256 tokens x 256 output features (two
+// heads); a wave owns 128 tokens x one head as 4 x 4 accumulators of
+// v_mfma_f32_32x32x16_bf16 with the features on the accumulator rows.  A lane
+// then holds, for one token, features 8j + 4(l/32) + {0..3} of every 32-block:
+// both members (i, i + 64) of a rotary pair sit in the same lane and register
+// index, and four consecutive features make one 8-byte piece of the output row.
+//
+// The contraction runs in steps of 32 through a 5-stage LDS ring filled by
+// direct global->LDS loads (16 bytes per lane; the gather is free, every lane
+// carries its own row pointer).  A row of a stage is 64 bytes; the 16-byte
+// chunk c of row r is stored at position c ^ ((r >> 2) & 3), which makes both
+// the 1 KB-contiguous fill and the ds_read_b128 of the MFMA operands
+// conflict-free.  One barrier per stage, placed between the two 16-wide
+// contraction sub-steps so that the operands of the next stage are already in
+// flight while the second sub-step's MFMAs run.
+//
+// Tiles are numbered so that each XCD (workgroup id mod 8) works through its own
+// contiguous run of tiles, 8 token tiles deep, and its L2 sees few distinct
+// operand panels at a time.
+#include "proj_common.h"
+
+namespace pkv {
+
+namespace {
+
+constexpr int D = 128;
+constexpr int T = kProjDmaTile;                  // tokens and features per tile
+constexpr int BK = 32;                           // contraction per stage
+constexpr int NS = 5;                            // LDS stages
+constexpr int kRowBytes = BK * 2;                // 64
+constexpr int kOperandBytes = T * kRowBytes;     // 16 KB: 256 rows of one operand
+constexpr int kStageBytes = 2 * kOperandBytes;   // token rows, then feature rows
+constexpr int kLdsBytes = NS * kStageBytes;      // 160 KB, all of a CU's LDS
+constexpr int kEpiStride = 272;                  // bytes per token of the store staging
+constexpr int kGroup = 8;                        // token tiles per group
+
+// 16 bytes per lane from global memory straight into LDS: lane i of the wave
+// writes LDS bytes [lds_base + 16 i, +16); lds_base must be wave-uniform.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, off"
+        :
+        : "s"(lds_base), "v"(gptr)
+        : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int n_tok_tiles,
+                                                              int n_tiles, int per_xcd) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hh = lane >> 5, l32 = lane & 31;
+    const int wt = wave >> 1, wf = wave & 1;
+
+    // ---- which tile --------------------------------------------------------------
+    const int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (logical >= n_tiles) return;
+    const int n_feat_tiles = p.tile_begin[3];
+    const int per_group = kGroup * n_feat_tiles;
+    const int group = logical / per_group;
+    const int first_tok = group * kGroup;
+    const int rows_in_group = min(kGroup, n_tok_tiles - first_tok);
+    const int within = logical - group * per_group;
+    const int tok_tile = first_tok + within % rows_in_group;
+    const int ft = within / rows_in_group;
+    int mat = 0;
+    if (ft >= p.tile_begin[1]) mat = 1;
+    if (ft >= p.tile_begin[2]) mat = 2;
+    const int feat0 = (ft - p.tile_begin[mat]) * T;   // first output feature of the tile
+    const bf16_t* w = p.w[mat];
+    bf16_t* out = p.out[mat];
+    const int heads_out = mat == 0 ? p.hq : p.hkv;
+    const int row0 = tok_tile * T;
+
+    // ---- fill side: wave w, instruction j covers rows 16 (4w + j) .. + 16 ------------
+    const int sw = (lane & 3) ^ ((lane >> 4) & 3);   // global chunk that lands at lane & 3
+    const bf16_t* xptr[4];
+    const bf16_t* wptr[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = (wave * 4 + j) * 16 + (lane >> 2);
+        const int gr = min(row0 + r, p.m - 1);
+        const int64_t src_row = p.row_idx ? p.row_idx[gr] : gr;
+        xptr[j] = p.hidden + src_row * p.hid + sw * 8;
+        wptr[j] = w + (int64_t)(feat0 + r) * p.hid + sw * 8;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(lds0 + wave * 4 * 1024);
+    // one fill instruction: 16 rows of the token operand (which = 0) or of the
+    // feature operand (which = 1).  adv is BK, or 0 once the last stage has been
+    // requested: the ring then keeps re-reading that stage into slots nobody reads
+    // any more, which keeps the loop and its wait counts uniform.
+    auto issue_one = [&](int stage, int j, int which, int adv) {
+        const uint32_t base = lds_fill + stage * kStageBytes + j * 1024;
+        if (which == 0) {
+            dma16(xptr[j], base);
+            xptr[j] += adv;
+        } else {
+            dma16(wptr[j], base + kOperandBytes);
+            wptr[j] += adv;
+        }
+    };
+
+    // ---- read side -----------------------------------------------------------------
+    // operand of row r, sub-step ks: chunk ks*2 + hh at position chunk ^ ((r >> 2) & 3)
+    int off_x[2], off_w[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int pos = (ks * 2 + hh) ^ ((l32 >> 2) & 3);
+        off_x[ks] = (wt * 128 + l32) * kRowBytes + pos * 16;
+        off_w[ks] = kOperandBytes + (wf * 128 + l32) * kRowBytes + pos * 16;
+    }
+    bf16x8 fx[2][4], fw[2][4];
+    auto load_frags = [&](int stage, int ks, int slot) {
+        const unsigned char* sb = smem + stage * kStageBytes;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            fw[slot][b] = *reinterpret_cast<const bf16x8*>(sb + off_w[ks] + b * 32 * kRowBytes);
+            fx[slot][b] = *reinterpret_cast<const bf16x8*>(sb + off_x[ks] + b * 32 * kRowBytes);
+        }
+    };
+
+    f32x16 acc[4][4];   // [feature block][token block]
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
+    // 16 MFMAs of one contraction sub-step; one fill instruction goes out after every
+    // fourth MFMA (half a stage per sub-step), so the memory pipeline sees a steady
+    // trickle instead of a burst that stalls the wave
+    auto mfma16 = [&](int slot, int fill_stage, int j0, int adv) {
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) {
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb)
+                acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[slot][fb], fx[slot][tb],
+                                                                      acc[fb][tb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_one(fill_stage, j0 + (fb >> 1), fb & 1, adv);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    const int n_k = p.hid / BK;   // >= NS, checked by the launcher
+    // prologue: stages 0 .. NS-3 and the first half of stage NS-2 in flight
+#pragma unroll
+    for (int s = 0; s < NS - 2; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            issue_one(s, j, 0, BK);
+            issue_one(s, j, 1, BK);
+        }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        issue_one(NS - 2, j, 0, BK);
+        issue_one(NS - 2, j, 1, BK);
+    }
+    wait_vm<8 * (NS - 3) + 4>();  // stage 0 of this wave has landed
+    __syncthreads();              // ... and everyone's
+    load_frags(0, 0, 0);
+    int st_cur = 0;               // t mod NS
+    for (int t = 0; t < n_k; ++t) {
+        const int st_next = st_cur + 1 == NS ? 0 : st_cur + 1;
+        const int st_fill = st_cur == 0 ? NS - 1 : st_cur - 1;          // (t + NS - 1) mod NS
+        const int st_fill_b = st_fill == 0 ? NS - 1 : st_fill - 1;      // (t + NS - 2) mod NS
+        load_frags(st_cur, 1, 1);
+        // second half of the fill of stage t + NS - 2 (its slot was freed one barrier ago)
+        mfma16(0, st_fill_b, 2, t + NS - 1 < n_k ? BK : 0);
+        wait_vm<8 * (NS - 3)>();  // stage t+1 has landed; the younger ones stay in flight
+        __syncthreads();          // ... for everyone; and everyone is done with stage t-1
+        load_frags(st_next, 0, 0);
+        // first half of the fill of stage t + NS - 1, into the slot of stage t-1
+        mfma16(1, st_fill, 0, t + NS < n_k ? BK : 0);
+        st_cur = st_next;
+    }
+    wait_vm<0>();                 // the ring's trailing fills must not land in the staging
+
+    // ---- epilogue: rotate pairs in registers, round once, stage, store 16 B per lane ----
+    if (out == nullptr) return;   // uniform over the workgroup
+    __syncthreads();              // LDS stages are free
+    const int head = feat0 / D + wf;
+    const bool rotate = mat != 2;
+    unsigned char* epi = smem + wave * (64 * kEpiStride);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int tbl = 0; tbl < 2; ++tbl) {
+            const int tb = half * 2 + tbl;
+            const int row = min(row0 + wt * 128 + tb * 32 + l32, p.m - 1);
+            const float4* cs = reinterpret_cast<const float4*>(p.cs + (int64_t)row * (D / 2));
+            unsigned char* erow = epi + (tbl * 32 + l32) * kEpiStride;
+#pragma unroll
+            for (int fbp = 0; fbp < 2; ++fbp)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int i0 = fbp * 32 + 8 * j + 4 * hh;   // pair index of element 0
+                    float a[4], b[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        a[e] = acc[fbp][tb][4 * j + e];
+                        b[e] = acc[fbp + 2][tb][4 * j + e];
+                    }
+                    if (rotate) {
+                        const float4 t0 = cs[i0 / 2], t1 = cs[i0 / 2 + 1];
+                        const float c[4] = {t0.x, t0.z, t1.x, t1.z};
+                        const float s[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float ra = a[e] * c[e] - b[e] * s[e];
+                            const float rb = b[e] * c[e] + a[e] * s[e];
+                            a[e] = ra;
+                            b[e] = rb;
+                        }
+                    }
+                    bf16x4 va, vb;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        va[e] = (bf16_t)a[e];
+                        vb[e] = (bf16_t)b[e];
+                    }
+                    *reinterpret_cast<bf16x4*>(erow + i0 * 2) = va;
+                    *reinterpret_cast<bf16x4*>(erow + (i0 + D / 2) * 2) = vb;
+                }
+        }
+        // the wave's own 64 tokens x 256 B, now 16 B per lane and 256 B per row
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+            const int idx = it * 64 + lane;
+            const int tok = idx >> 4, ch = idx & 15;
+            const int row = row0 + wt * 128 + half * 64 + tok;
+            const uint4 v = *reinterpret_cast<const uint4*>(epi + tok * kEpiStride + ch * 16);
+            if (row < p.m)
+                *reinterpret_cast<uint4*>(out + ((int64_t)row * heads_out + head) * D + ch * 8) = v;
+        }
+    }
+}
+
+}  // namespace
+
+bool proj_dma128_supported(const pkv_layer_cfg& cfg, int64_t m) {
+    return cfg.dtype == PKV_BF16 && cfg.head_dim == D && cfg.hidden % BK == 0 &&
+           cfg.hidden / BK >= NS && cfg.n_q_heads % 2 == 0 && cfg.n_kv_heads % 2 == 0 &&
+           m > 0 && m < (1 << 30);
+}
+
+pkv_status launch_proj_dma128(const ProjParams& p, hipStream_t st) {
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(qkv_proj_dma128_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes) != hipSuccess)
+            return PKV_ERR_LAUNCH;
+        configured = true;
+    }
+    const int n_tok_tiles = (int)ceil_div(p.m, T);
+    const int64_t n_tiles = (int64_t)n_tok_tiles * p.tile_begin[3];
+    if (n_tiles == 0) return PKV_OK;
+    if (n_tiles > (1 << 30)) return PKV_ERR_SHAPE;
+    const int per_xcd = (int)ceil_div(n_tiles, 8);
+    hipLaunchKernelGGL(qkv_proj_dma128_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256),
+                       kLdsBytes, st, p, n_tok_tiles, (int)n_tiles, per_xcd);
+    return launch_status();
+}
+
+}  // namespace pkv

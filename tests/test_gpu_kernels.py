@@ -199,7 +199,8 @@ def test_query_score_custom_scale(gpu_device):
 @pytest.mark.parametrize("dtype,m,hq,hkv,d,hid,theta", [
     ("f32", 220, 4, 4, 64, 256, 10000.0), ("f32", 37, 4, 2, 32, 64, 10000.0),
     ("bf16", 300, 32, 8, 128, 1024, 500000.0), ("bf16", 65, 4, 4, 64, 128, 500000.0),
-    ("bf16", 129, 10, 2, 128, 512, 500000.0)])
+    ("bf16", 129, 10, 2, 128, 512, 500000.0), ("bf16", 257, 4, 2, 128, 160, 500000.0),
+    ("bf16", 1, 2, 2, 128, 4096, 500000.0)])
 def test_gather_qkv_proj_matches_oracle(gpu_device, dtype, m, hq, hkv, d, hid, theta):
     cfg = lcfg(dtype, hq, hkv, d, hid, theta)
     n_rows = 2 * m + 11
@@ -265,7 +266,8 @@ def test_sparse_row_attn_matches_oracle(gpu_device, dtype, m, n_keys, hq, hkv, d
     args = (dev(q, dtype, gpu_device), dev(kc, dtype, gpu_device), dev(vc, dtype, gpu_device))
     api.pkv_sparse_row_attn(cfg, *args, torch.from_numpy(pos).to(gpu_device), out, lse, ws=ws)
     assert rel_err(host(out), want) <= TOL[dtype]
-    assert np.abs(host(lse) - want_lse).max() <= 1e-3
+    # bf16: the normaliser sums bf16-rounded probabilities (2^-9 relative each)
+    assert np.abs(host(lse) - want_lse).max() <= (4e-3 if dtype == "bf16" else 1e-3)
     # row order does not matter: a shuffled row set gives the same rows
     perm = g.permutation(m)
     out2 = torch.empty_like(out)
