@@ -28,6 +28,10 @@ if ROOT not in sys.path:
 from paper_2602_02579_amd import api, pipeline, synth  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
+# HBM bytes per pkv_sparse_row_attn launch (V^T pre-pass + main kernel), from the
+# FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/hot_path_cfg3_hbm_traffic.txt
+# (counters cannot be read from inside this process; the figure is for that workload only)
+MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 1.0866e9}
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
@@ -82,7 +86,7 @@ def build_gpu_workload(cfg, device):
 # CPU baseline: the oracle as it stands, on a bounded sample
 # --------------------------------------------------------------------------
 
-def cpu_baseline(cfg, row_stride=4):
+def cpu_baseline(cfg, row_stride=2):
     """Times the CPU oracle on the same seeded workload.  Restore, query
     projection, score and selection run in full; the row-wise steps
     (projection, scatter, attention) run on every `row_stride`-th recomputed
@@ -308,7 +312,8 @@ def main():
         "sparse_row_attn_tflops": round(achieved, 2),
         "roofline": {"kernel": "pkv_sparse_row_attn", "bound": "mfma",
                      "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
-                     "frac": round(achieved / peak, 4), "traffic": None,
+                     "frac": round(achieved / peak, 4),
+                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(cfg.name),
                      "flops_per_launch": flops, "avg_launch_s": t_attn},
         "breakdown": breakdown,
     }
