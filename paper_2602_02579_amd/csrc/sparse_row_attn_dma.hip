@@ -185,6 +185,28 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
             dma16(gb_, voff_v[i], lb_ + i * 1024);                                       \
     }
 
+    // The eight fill instructions of a tile (K tile J+3, V^T tile J+2) go out in four
+    // pairs spread over the tile's four scheduling regions: a burst of eight from each
+    // of the four waves fills the memory pipeline's queue and stalls the waves.
+    const bf16_t* gbk_;
+    const bf16_t* gbv_;
+    uint32_t kofs_[4];
+#define PKV_DMA_PREP(J)                                                                  \
+    {                                                                                    \
+        const int tk_ = min((J) + 3, n_iter - 1);                                        \
+        const int t0k_ = tk_ * kBN;                                                      \
+        gbk_ = k_head + (int64_t)t0k_ * p.hkv * D;                                       \
+        const int last_ = p.n_keys - 1 - t0k_;  /* rows past the cache re-read its last */ \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                    \
+            kofs_[i] = (uint32_t)min(krow[i], last_) * k_row_bytes + kchunk16[i];        \
+        gbv_ = v_head + min((J) + 2, n_iter - 1) * kBN;                                  \
+    }
+#define PKV_DMA_PAIR(I, SDK, SDV)                                                        \
+    {                                                                                    \
+        dma16(gbk_, kofs_[I], lds_k_wave + (SDK) * kStageK + (I) * 1024);                \
+        dma16(gbv_, voff_v[I], lds_v_wave + (SDV) * kStageV + (I) * 1024);               \
+    }
+
     // ---- LDS -> register operand addresses (bytes inside a stage) ------------------------
     // A-row i of a 32-key block reads key swap_bits23(i) of that block, so that
     // accumulator register r of lane half hh holds key 16*(r/8) + 8*hh + r%8.
@@ -228,7 +250,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         }                                                                                \
     }
 
-    // mask (optional) and maximum of a score buffer; raises `grow`
+    // mask (optional) and this lane's maximum of a score buffer (its 16 of the 32
+    // keys); raises `grow`.  Nothing crosses lanes here: a shuffle and its wait would
+    // idle the matrix pipe, the wave being the only one on its SIMD.
 #define PKV_STATS(S, T0, MASK)                                                           \
     _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) {                                   \
         if (MASK) {                                                                      \
@@ -239,8 +263,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         }                                                                                \
         float mx_ = S[cb][0];                                                            \
         _Pragma("unroll") for (int r = 1; r < 16; ++r) mx_ = fmaxf(mx_, S[cb][r]);       \
-        mx_ = fmaxf(mx_, __shfl_xor(mx_, 32, 64));                                       \
-        m_new[cb] = fmaxf(m_run[cb], mx_);                                               \
+        mx_lane[cb] = mx_;                                                               \
         grow = grow || (mx_ * c2 - msc[cb] > kLazy);                                     \
     }
 
@@ -253,6 +276,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 #define PKV_RESCALE()                                                                    \
     if (__builtin_expect(__any(grow), 0)) {                                              \
         _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) {                               \
+            m_new[cb] = fmaxf(m_run[cb],                                                 \
+                              fmaxf(mx_lane[cb], __shfl_xor(mx_lane[cb], 32, 64)));      \
             const float ms_ = m_new[cb] == -INFINITY ? 0.f : m_new[cb];                  \
             const float corr_ = __builtin_amdgcn_exp2f((m_run[cb] - ms_) * c2);          \
             l_run[cb] *= corr_;                                                          \
@@ -266,8 +291,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     // one 32-key sub-step u: CUR holds S^T(u); NXT receives S^T(u+1) (operands
     // already in ka); (KST, KH) name the K half tile of sub-step u+2, (VST, VH)
     // the V^T half tile of sub-step u.
-#define PKV_SUBSTEP(CUR, NXT, KST, KH, VST, VH, T0_NEXT, MASK)                           \
+#define PKV_SUBSTEP(CUR, NXT, KST, KH, VST, VH, T0_NEXT, MASK, DI, SDK, SDV)             \
     {                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+        PKV_DMA_PAIR(DI, SDK, SDV)                                                       \
         __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_LOAD_VA(VST, VH)                                                             \
         PKV_QK(NXT)                                                                      \
@@ -279,14 +306,15 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
                 rs_ += e_;                                                               \
                 pb_[r / 8][cb][r % 8] = (bf16_t)e_;                                      \
             }                                                                            \
-            rs_ += __shfl_xor(rs_, 32, 64);                                              \
-            l_run[cb] += rs_;                                                            \
+            l_run[cb] += rs_;   /* this lane's 16 keys; halves meet in the epilogue */    \
         }                                                                                \
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);                          \
         _Pragma("unroll") for (int i_ = 0; i_ < 2 * KC; ++i_) {                          \
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           \
             __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);                           \
         }                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+        PKV_DMA_PAIR((DI) + 1, SDK, SDV)                                                 \
         __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_LOAD_KA(KST, KH)                                                             \
         _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                 \
@@ -309,11 +337,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 #define PKV_TILE(J, SK1, SV0, SDK, SDV, MASK)                                            \
     {                                                                                    \
         const int t0_tile_ = (J) * kBN;                                                  \
-        PKV_DMA_K((J) + 3, SDK)                                                          \
-        PKV_DMA_V((J) + 2, SDV)                                                          \
-        PKV_SUBSTEP(s_a, s_b, SK1, 0, SV0, 0, t0_tile_ + 32, MASK)                       \
+        PKV_DMA_PREP(J)                                                                  \
+        PKV_SUBSTEP(s_a, s_b, SK1, 0, SV0, 0, t0_tile_ + 32, MASK, 0, SDK, SDV)          \
         PKV_RESCALE()                                                                    \
-        PKV_SUBSTEP(s_b, s_a, SK1, 1, SV0, 1, t0_tile_ + 64, MASK)                       \
+        PKV_SUBSTEP(s_b, s_a, SK1, 1, SV0, 1, t0_tile_ + 64, MASK, 2, SDK, SDV)          \
         wait_vm<8>();   /* K(J+2), V^T(J+1) have landed; 8 newer loads stay in flight */ \
         __syncthreads();                                                                 \
         PKV_RESCALE()                                                                    \
@@ -326,7 +353,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     wait_vm<0>();
     __syncthreads();
     constexpr float kLazy = 40.f;
-    float m_new[2];
+    float m_new[2], mx_lane[2];
     float msc[2] = {0.f, 0.f};   // reference maximum times c2 (0 while it is -inf)
     bool grow = false;
     PKV_LOAD_KA(0, 0)
@@ -336,7 +363,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     // first sub-step: nothing accumulated yet, the reference is simply its maximum
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
-        m_run[cb] = m_new[cb];
+        m_run[cb] = fmaxf(mx_lane[cb], __shfl_xor(mx_lane[cb], 32, 64));
         msc[cb] = (m_run[cb] == -INFINITY ? 0.f : m_run[cb]) * c2;
     }
     grow = false;
@@ -362,6 +389,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 
 #undef PKV_DMA_K
 #undef PKV_DMA_V
+#undef PKV_DMA_PREP
+#undef PKV_DMA_PAIR
 #undef PKV_LOAD_KA
 #undef PKV_LOAD_VA
 #undef PKV_QK
@@ -371,11 +400,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 #undef PKV_TILE
 
     // ---- epilogue ----------------------------------------------------------------------
+    float l_tot[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) l_tot[cb] = l_run[cb] + __shfl_xor(l_run[cb], 32, 64);
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         if (!valid[cb]) continue;
         const int64_t colg = (int64_t)row[cb] * p.hq + head[cb];
-        const float inv = 1.f / l_run[cb];
+        const float inv = 1.f / l_tot[cb];
         bf16_t* op = p.out + colg * D + 4 * hh;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -386,7 +418,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
                 for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(o_acc[db][cb][4 * r4 + e] * inv);
                 *reinterpret_cast<bf16x4*>(op + db * 32 + r4 * 8) = v;
             }
-        if (p.lse && hh == 0) p.lse[colg] = m_run[cb] * p.scale + logf(l_run[cb]);
+        if (p.lse && hh == 0) p.lse[colg] = m_run[cb] * p.scale + logf(l_tot[cb]);
     }
 }
 
