@@ -151,6 +151,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
     wg /= p.hkv;
     const int split = wg % p.n_splits;
     const int tile = p.n_tiles - 1 - wg / p.n_splits;
+    // repair pass: only the tiles that the pipelined kernel marked
+    if (p.flags && p.flags[tile * p.hkv + g] == 0) return;
 
     // ---- my two columns ----------------------------------------------------
     int limit[2], row[2], head[2];
@@ -421,6 +423,17 @@ bool mfma_attn_supported(const pkv_layer_cfg& cfg) {
 
 int64_t pad64(int64_t n) { return (n + 63) & ~(int64_t)63; }
 
+// workspace: V^T [hkv, D, n_pad] (rounded up to 256 bytes), then one int per
+// (row tile, kv head) for the repair pass
+size_t attn_vt_bytes(const pkv_layer_cfg& cfg, int64_t n_keys) {
+    const size_t b = (size_t)cfg.n_kv_heads * cfg.head_dim * pad64(n_keys) * sizeof(bf16_t);
+    return (b + 255) & ~(size_t)255;
+}
+size_t attn_flag_bytes(const pkv_layer_cfg& cfg, int64_t m) {
+    const int bm = 256 / (cfg.n_q_heads / cfg.n_kv_heads);
+    return (size_t)ceil_div(m, bm) * cfg.n_kv_heads * sizeof(int);
+}
+
 template <int D, bool kPV>
 pkv_status launch_attn_mfma(const AttnParams& p, hipStream_t st) {
     static bool configured = false;  // per process; the attribute is per function
@@ -441,9 +454,8 @@ pkv_status launch_attn_mfma(const AttnParams& p, hipStream_t st) {
 }  // namespace
 
 size_t sparse_row_attn_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m) {
-    (void)m;
     if (!mfma_attn_supported(cfg)) return 0;
-    return (size_t)cfg.n_kv_heads * cfg.head_dim * pad64(n_keys) * sizeof(bf16_t);
+    return attn_vt_bytes(cfg, n_keys) + attn_flag_bytes(cfg, m);
 }
 
 // Per-column (max, sum) partials of softmax(q k^T * scale) over keys
@@ -509,7 +521,13 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         p.fixed_limit = -1;
         p.scale = scale;
         p.scale_log2 = scale * 1.4426950408889634f;
-        return d == 128 ? launch_attn_dma128(p, st) : launch_attn_mfma<64, true>(p, st);
+        if (d != 128) return launch_attn_mfma<64, true>(p, st);
+        // pipelined kernel with a fixed softmax reference per column, then the exact
+        // kernel on the tiles it marked (normally none: those workgroups exit at once)
+        p.flags = reinterpret_cast<int*>((unsigned char*)ws + attn_vt_bytes(cfg, n_keys));
+        const pkv_status rc = launch_attn_dma128(p, st);
+        if (rc != PKV_OK) return rc;
+        return launch_attn_mfma<128, true>(p, st);
     }
     const int block = d <= 64 ? 64 : (d <= 128 ? 128 : 256);
     const dim3 grid((unsigned)m, (unsigned)cfg.n_q_heads);

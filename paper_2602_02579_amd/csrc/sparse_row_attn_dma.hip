@@ -13,10 +13,9 @@
 //   inside one instruction stream.  On this chip a SIMD issues one VALU-class
 //   instruction per 4 cycles and an MFMA 32x32x16 holds the matrix pipe for 8
 //   such slots, so at most ~7 other instructions per MFMA are free.  The keys
-//   of a 64-key tile are processed as two 32-key sub-steps; in sub-step u
-//       phase A: S^T(u+1) MFMAs   next to   P(u) = exp2(S^T(u) c - ref)   (VALU)
-//       phase B: O^T += V^T P^T(u) MFMAs   next to   mask / max of S^T(u+1)
-//   with sched_group_barrier pinning one MFMA per handful of VALU instructions.
+//   of a 64-key tile are processed as two 32-key sub-steps of 32 MFMAs; the
+//   softmax of a sub-step is cut into 16 pairs of scores and one pair follows
+//   every second MFMA (see PKV_SUBSTEP), pinned with sched_barrier.
 // * LDS -> register operand loads are issued one phase ahead of their MFMAs.
 // * K and V^T tiles reach LDS by direct global->LDS loads (no staging
 //   registers, no ds_write), 4 stages deep, issued three tiles ahead; the only
@@ -25,9 +24,9 @@
 //   address side of the load) keeps the MFMA operand reads conflict free.
 //   The loads are inline asm because the compiler would otherwise make every
 //   LDS read wait for all outstanding global->LDS loads.
-// * The reference maximum of a column is raised only when a score exceeds it
-//   by 2^40 (see PKV_RESCALE), so the output accumulators never leave the
-//   MFMA-only registers in the hot loop.
+// * The reference maximum of a column is fixed after its first 32 keys (see
+//   PKV_ACC): no maximum, no rescaling and no branch in the hot loop; tiles whose
+//   probabilities leave the safe range are marked and redone by the exact kernel.
 #include "attn_common.h"
 
 namespace pkv {
@@ -105,7 +104,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     // (wave-uniform values are moved to scalar registers explicitly: they feed
     // the scalar operands of the global->LDS loads and the loop control)
     const int n_iter = __builtin_amdgcn_readfirstlane((key_end + kBN - 1) / kBN);
-    if (n_iter <= 0) return;  // block-uniform: the tile has no valid row
+    if (n_iter <= 0) {        // block-uniform: the tile has no valid row
+        if (tid == 0) p.flags[tile * p.hkv + g] = 0;
+        return;
+    }
     // sub-steps [0, u_unm) lie entirely at or below every limit of this wave
     const int u_unm = __builtin_amdgcn_readfirstlane(lmin == 0x7fffffff ? 0 : (lmin + 1) / 32);
 
@@ -224,6 +226,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 
     f32x16 s_a[2], s_b[2];   // S^T of one 32-key sub-step, per column block
     bf16x8 ka[KC], va[2][DB];
+    bf16x8 pb[2][2];         // P^T of the current sub-step: [16-key half][column block]
+    float rs[2] = {0.f, 0.f};  // this lane's sum of the probabilities being produced
+    float msc[2];            // reference maximum times c2 (0 while it is -inf)
+    constexpr float kGrow = 1.0e24f;   // ~2^80
+    float rs_max = 0.f;
 
     // operands of the 32-key half H of the K tile in stage ST
 #define PKV_LOAD_KA(ST, H)                                                               \
@@ -237,99 +244,92 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         va[kk][db] = *reinterpret_cast<const bf16x8*>(                                   \
             smem + NS * kStageK + (ST) * kStageV + db * 32 * 128 + vaddr[2 * (H) + kk]);
 
-    // S^T = K Q^T for the 32 keys whose operands sit in ka
-#define PKV_QK(S)                                                                        \
+    // The softmax of a sub-step is cut into pairs of scores (one packed bf16
+    // conversion each): pair PI of column block CB of score buffer S whose first
+    // key is T0.  p = exp2(s c2 - ref) with the reference of the column block;
+    // masked keys give exp2(-inf) = 0.
+#define PKV_SM_PAIR(S, CB, PI, T0, MASK)                                                 \
     {                                                                                    \
-        const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,                       \
-                           0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};                      \
-        S[0] = mfma32(ka[0], qreg[0][0], z_);                                            \
-        S[1] = mfma32(ka[0], qreg[1][0], z_);                                            \
-        _Pragma("unroll") for (int kc = 1; kc < KC; ++kc) {                              \
-            S[0] = mfma32(ka[kc], qreg[0][kc], S[0]);                                    \
-            S[1] = mfma32(ka[kc], qreg[1][kc], S[1]);                                    \
-        }                                                                                \
-    }
-
-    // mask (optional) and this lane's maximum of a score buffer (its 16 of the 32
-    // keys); raises `grow`.  Nothing crosses lanes here: a shuffle and its wait would
-    // idle the matrix pipe, the wave being the only one on its SIMD.
-#define PKV_STATS(S, T0, MASK)                                                           \
-    _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) {                                   \
+        float x0_ = S[CB][2 * (PI)], x1_ = S[CB][2 * (PI) + 1];                          \
         if (MASK) {                                                                      \
-            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                             \
-                const int key_ = (T0) + 16 * (r / 8) + 8 * hh + (r % 8);                 \
-                if (key_ > limit[cb]) S[cb][r] = -INFINITY;                              \
-            }                                                                            \
+            const int key_ = (T0) + 16 * ((PI) / 4) + 8 * hh + (2 * (PI)) % 8;           \
+            if (key_ > limit[CB]) x0_ = -INFINITY;                                       \
+            if (key_ + 1 > limit[CB]) x1_ = -INFINITY;                                   \
         }                                                                                \
-        float mx_ = S[cb][0];                                                            \
-        _Pragma("unroll") for (int r = 1; r < 16; ++r) mx_ = fmaxf(mx_, S[cb][r]);       \
-        mx_lane[cb] = mx_;                                                               \
-        grow = grow || (mx_ * c2 - msc[cb] > kLazy);                                     \
+        const float e0_ = __builtin_amdgcn_exp2f(x0_ * c2 - msc[CB]);                    \
+        const float e1_ = __builtin_amdgcn_exp2f(x1_ * c2 - msc[CB]);                    \
+        rs[CB] += e0_;                                                                   \
+        rs[CB] += e1_;                                                                   \
+        pb[(PI) / 4][CB][(2 * (PI)) % 8] = (bf16_t)e0_;                                  \
+        pb[(PI) / 4][CB][(2 * (PI)) % 8 + 1] = (bf16_t)e1_;                              \
     }
 
-    // The reference maximum m_run of a column is NOT the running maximum: it is
-    // raised (and the accumulators rescaled) only when a score exceeds it by more
-    // than kLazy in the exp2 domain.  Probabilities then reach 2^kLazy at most,
-    // far inside the range of bf16/fp32, and relative precision does not depend
-    // on the reference.  The rescale is therefore a cold path, and the output
-    // accumulators can stay in MFMA-only registers throughout the hot loop.
-#define PKV_RESCALE()                                                                    \
-    if (__builtin_expect(__any(grow), 0)) {                                              \
-        _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) {                               \
-            m_new[cb] = fmaxf(m_run[cb],                                                 \
-                              fmaxf(mx_lane[cb], __shfl_xor(mx_lane[cb], 32, 64)));      \
-            const float ms_ = m_new[cb] == -INFINITY ? 0.f : m_new[cb];                  \
-            const float corr_ = __builtin_amdgcn_exp2f((m_run[cb] - ms_) * c2);          \
-            l_run[cb] *= corr_;                                                          \
-            _Pragma("unroll") for (int db = 0; db < DB; ++db)                            \
-            _Pragma("unroll") for (int r = 0; r < 16; ++r) o_acc[db][cb][r] *= corr_;    \
-            m_run[cb] = m_new[cb];                                                       \
-            msc[cb] = ms_ * c2;                                                          \
-        }                                                                                \
+    // The reference maximum m_run of a column is NOT the running maximum: it is the
+    // maximum of the column's first 32 keys and stays fixed.  The hot loop takes no
+    // maximum and never touches the output accumulators with the VALU.  Relative
+    // precision does not depend on the reference; what can go wrong is range, when a
+    // later score exceeds the reference by more than ~2^80 in the exp2 domain.  So the
+    // sums of the probabilities are watched: a partial sum beyond kGrow (or a total
+    // that is not finite) marks the tile, and the launcher runs the exact kernel
+    // (running maximum, rescaling) on marked tiles afterwards.
+#define PKV_ACC(CB)                                                                      \
+    {                                                                                    \
+        l_run[CB] += rs[CB];                                                             \
+        rs_max = fmaxf(rs_max, rs[CB]);                                                  \
+        rs[CB] = 0.f;                                                                    \
     }
 
-    // one 32-key sub-step u: CUR holds S^T(u); NXT receives S^T(u+1) (operands
-    // already in ka); (KST, KH) name the K half tile of sub-step u+2, (VST, VH)
-    // the V^T half tile of sub-step u.
-#define PKV_SUBSTEP(CUR, NXT, KST, KH, VST, VH, T0_NEXT, MASK, DI, SDK, SDV)             \
+    // One 32-key sub-step u.  CUR holds S^T(u), NXT receives S^T(u+1) (operands
+    // already in ka); (KST, KH) name the K half tile of sub-step u+2, (VST, VH) the
+    // V^T half tile of sub-step u; T0 is the first key of sub-step u.  The first
+    // four pairs of P(u), column block 0, were formed at the end of sub-step u-1.
+    // 32 MFMAs, each pair of them followed by one softmax pair, so that the VALU
+    // work is spread evenly under the matrix pipe:
+    //    MFMA  1-16  S^T(u+1)            | P(u): block 0 pairs 4-7, block 1 pairs 0-3
+    //    MFMA 17-24  O^T += V^T P^T, b.0 | P(u): block 1 pairs 4-7
+    //    MFMA 25-32  O^T += V^T P^T, b.1 | P(u+1): block 0 pairs 0-3
+#define PKV_SUBSTEP(CUR, NXT, KST, KH, VST, VH, T0, MASK, DI, SDK, SDV)                  \
     {                                                                                    \
         __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_DMA_PAIR(DI, SDK, SDV)                                                       \
         __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_LOAD_VA(VST, VH)                                                             \
-        PKV_QK(NXT)                                                                      \
-        bf16x8 pb_[2][2];                                                                \
-        _Pragma("unroll") for (int cb = 0; cb < 2; ++cb) {                               \
-            float rs_ = 0.f;                                                             \
-            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                             \
-                const float e_ = __builtin_amdgcn_exp2f(CUR[cb][r] * c2 - msc[cb]);      \
-                rs_ += e_;                                                               \
-                pb_[r / 8][cb][r % 8] = (bf16_t)e_;                                      \
-            }                                                                            \
-            l_run[cb] += rs_;   /* this lane's 16 keys; halves meet in the epilogue */    \
+        {                                                                                \
+            const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,                   \
+                               0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};                  \
+            NXT[0] = mfma32(ka[0], qreg[0][0], z_);                                      \
+            NXT[1] = mfma32(ka[0], qreg[1][0], z_);                                      \
         }                                                                                \
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);                          \
-        _Pragma("unroll") for (int i_ = 0; i_ < 2 * KC; ++i_) {                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           \
-            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);                           \
+        PKV_SM_PAIR(CUR, 0, 4, T0, MASK)                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+        _Pragma("unroll") for (int kc = 1; kc < KC; ++kc) {                              \
+            NXT[0] = mfma32(ka[kc], qreg[0][kc], NXT[0]);                                \
+            NXT[1] = mfma32(ka[kc], qreg[1][kc], NXT[1]);                                \
+            if (kc < 4) { PKV_SM_PAIR(CUR, 0, 4 + kc, T0, MASK) }                        \
+            else { PKV_SM_PAIR(CUR, 1, kc - 4, T0, MASK) }                               \
+            __builtin_amdgcn_sched_barrier(0);                                           \
         }                                                                                \
+        PKV_ACC(0)                                                                       \
         __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_DMA_PAIR((DI) + 1, SDK, SDV)                                                 \
         __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_LOAD_KA(KST, KH)                                                             \
-        _Pragma("unroll") for (int kk = 0; kk < 2; ++kk)                                 \
-        _Pragma("unroll") for (int db = 0; db < DB; ++db) {                              \
-            o_acc[db][0] = mfma32(va[kk][db], pb_[kk][0], o_acc[db][0]);                 \
-            o_acc[db][1] = mfma32(va[kk][db], pb_[kk][1], o_acc[db][1]);                 \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                               \
+            const int kk_ = i_ >> 1, db_ = 2 * (i_ & 1);                                 \
+            o_acc[db_][0] = mfma32(va[kk_][db_], pb[kk_][0], o_acc[db_][0]);             \
+            o_acc[db_ + 1][0] = mfma32(va[kk_][db_ + 1], pb[kk_][0], o_acc[db_ + 1][0]); \
+            PKV_SM_PAIR(CUR, 1, 4 + i_, T0, MASK)                                        \
+            __builtin_amdgcn_sched_barrier(0);                                           \
         }                                                                                \
-        grow = false;                                                                    \
-        PKV_STATS(NXT, T0_NEXT, MASK)                                                    \
-        __builtin_amdgcn_sched_group_barrier(0x100, KC, 0);                              \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4 * DB; ++i_) {                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           \
-            __builtin_amdgcn_sched_group_barrier(0x002, (MASK) ? 8 : 3, 0);              \
-        }                                                                                \
+        PKV_ACC(1)                                                                       \
         __builtin_amdgcn_sched_barrier(0);                                               \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                               \
+            const int kk_ = i_ >> 1, db_ = 2 * (i_ & 1);                                 \
+            o_acc[db_][1] = mfma32(va[kk_][db_], pb[kk_][1], o_acc[db_][1]);             \
+            o_acc[db_ + 1][1] = mfma32(va[kk_][db_ + 1], pb[kk_][1], o_acc[db_ + 1][1]); \
+            PKV_SM_PAIR(NXT, 0, i_, (T0) + 32, MASK)                                     \
+            __builtin_amdgcn_sched_barrier(0);                                           \
+        }                                                                                \
     }
 
     // one 64-key tile J whose V^T sits in stage SV0 and whose successor's K sits in
@@ -338,12 +338,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     {                                                                                    \
         const int t0_tile_ = (J) * kBN;                                                  \
         PKV_DMA_PREP(J)                                                                  \
-        PKV_SUBSTEP(s_a, s_b, SK1, 0, SV0, 0, t0_tile_ + 32, MASK, 0, SDK, SDV)          \
-        PKV_RESCALE()                                                                    \
-        PKV_SUBSTEP(s_b, s_a, SK1, 1, SV0, 1, t0_tile_ + 64, MASK, 2, SDK, SDV)          \
+        PKV_SUBSTEP(s_a, s_b, SK1, 0, SV0, 0, t0_tile_, MASK, 0, SDK, SDV)               \
+        PKV_SUBSTEP(s_b, s_a, SK1, 1, SV0, 1, t0_tile_ + 32, MASK, 2, SDK, SDV)          \
         wait_vm<8>();   /* K(J+2), V^T(J+1) have landed; 8 newer loads stay in flight */ \
         __syncthreads();                                                                 \
-        PKV_RESCALE()                                                                    \
     }
 
     // ---- prologue ---------------------------------------------------------------------
@@ -352,27 +350,40 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     PKV_DMA_K(1, 1)
     wait_vm<0>();
     __syncthreads();
-    constexpr float kLazy = 40.f;
-    float m_new[2], mx_lane[2];
-    float msc[2] = {0.f, 0.f};   // reference maximum times c2 (0 while it is -inf)
-    bool grow = false;
     PKV_LOAD_KA(0, 0)
-    PKV_QK(s_a)
+    {
+        const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                           0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s_a[0] = mfma32(ka[0], qreg[0][0], z_);
+        s_a[1] = mfma32(ka[0], qreg[1][0], z_);
+#pragma unroll
+        for (int kc = 1; kc < KC; ++kc) {
+            s_a[0] = mfma32(ka[kc], qreg[0][kc], s_a[0]);
+            s_a[1] = mfma32(ka[kc], qreg[1][kc], s_a[1]);
+        }
+    }
     PKV_LOAD_KA(0, 1)            // operands of S^T(1)
-    PKV_STATS(s_a, 0, true)
     // first sub-step: nothing accumulated yet, the reference is simply its maximum
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
-        m_run[cb] = fmaxf(mx_lane[cb], __shfl_xor(mx_lane[cb], 32, 64));
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = 16 * (r / 8) + 8 * hh + (r % 8);
+            if (key <= limit[cb]) mx = fmaxf(mx, s_a[cb][r]);
+        }
+        m_run[cb] = fmaxf(mx, __shfl_xor(mx, 32, 64));
         msc[cb] = (m_run[cb] == -INFINITY ? 0.f : m_run[cb]) * c2;
     }
-    grow = false;
+#pragma unroll
+    for (int pi = 0; pi < 4; ++pi) PKV_SM_PAIR(s_a, 0, pi, 0, true)
     PKV_DMA_K(2, 2)
     PKV_DMA_V(1, 1)
 
     // ---- main loop: four tiles per trip so that every LDS stage is a constant ------------
-    // tile j is mask free when the statistics it computes (sub-steps 2j+1, 2j+2)
-    // are: 2j + 2 < u_unm
+    // tile j is mask free when every score it turns into a probability (sub-steps
+    // 2j, 2j+1 and the first pairs of 2j+2) lies at or below every limit of the wave:
+    // 2j + 2 < u_unm
     int n_unm = min(n_iter, max(0, (u_unm - 1) / 2));
     n_unm &= ~3;
     int j = 0;
@@ -393,9 +404,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 #undef PKV_DMA_PAIR
 #undef PKV_LOAD_KA
 #undef PKV_LOAD_VA
-#undef PKV_QK
-#undef PKV_STATS
-#undef PKV_RESCALE
+#undef PKV_SM_PAIR
+#undef PKV_ACC
 #undef PKV_SUBSTEP
 #undef PKV_TILE
 
@@ -403,6 +413,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     float l_tot[2];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) l_tot[cb] = l_run[cb] + __shfl_xor(l_run[cb], 32, 64);
+    {
+        const bool bad = !(rs_max < kGrow) || !(l_tot[0] < 3.0e38f) || !(l_tot[1] < 3.0e38f);
+        if (__any(bad) && lane == 0) s_red[wave] = 1 << 30;   // s_red held tile limits so far
+        else if (lane == 0) s_red[wave] = 0;
+        __syncthreads();
+        if (tid == 0)
+            p.flags[tile * p.hkv + g] = (s_red[0] | s_red[1] | s_red[2] | s_red[3]) != 0;
+    }
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         if (!valid[cb]) continue;

@@ -293,6 +293,38 @@ def test_sparse_row_attn_closed_forms(gpu_device):
         assert np.abs(got[:, h] - vc[0, h // 4]).max() <= 2e-2 * np.abs(vc[0]).max()
 
 
+def test_sparse_row_attn_scores_far_above_the_first_keys(gpu_device):
+    """Late keys whose scores exceed everything among a row's first 32 keys by
+    hundreds of nats: the fixed-reference fast path of the head_dim-128 kernel
+    cannot represent them and must hand the tile to the exact kernel."""
+    dtype, hq, hkv, d, n_keys, m = "bf16", 8, 2, 128, 700, 150
+    cfg = lcfg(dtype, hq, hkv, d)
+    g = np.random.default_rng(31)
+    q = rnd(32, (m, hq, d), dtype, 1.0)
+    kc, vc = rnd(33, (n_keys, hkv, d), dtype, 0.05), rnd(34, (n_keys, hkv, d), dtype)
+    # from key 300 on, keys of kv head 0 are aligned with the queries of rows 60..149
+    # of q head 1 (dot product ~ 128 * 16 -> ~180 nats after the 1/sqrt(d) scale);
+    # kv head 1 and the other rows stay ordinary
+    q[60:, 1, :] = 4.0
+    kc[300::7, 0, :] = 4.0
+    q, kc = synth.to_storage(q, dtype), synth.to_storage(kc, dtype)
+    pos = np.sort(g.choice(n_keys, m, replace=False)).astype(np.int32)
+    pos[-1] = n_keys - 1
+    want, want_lse = O.sparse_row_attn(q.astype(np.float64), kc.astype(np.float64),
+                                       vc.astype(np.float64), pos, dtype=dtype)
+    out = torch.empty((m, hq, d), dtype=torch.bfloat16, device=gpu_device)
+    lse = torch.empty((m, hq), dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, m), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    api.pkv_sparse_row_attn(cfg, dev(q, dtype, gpu_device), dev(kc, dtype, gpu_device),
+                            dev(vc, dtype, gpu_device), torch.from_numpy(pos).to(gpu_device),
+                            out, lse, ws=ws)
+    got, got_lse = host(out), host(lse)
+    assert np.isfinite(got).all() and np.isfinite(got_lse).all()
+    assert rel_err(got, want) <= TOL[dtype]
+    assert np.abs(got_lse - want_lse).max() <= 4e-3 * max(1.0, np.abs(want_lse).max() / 10)
+
+
 # ------------------------------------------------------------------ errors
 
 def test_host_checked_errors(gpu_device):
