@@ -231,6 +231,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     float msc[2];            // reference maximum times c2 (0 while it is -inf)
     constexpr float kGrow = 1.0e24f;   // ~2^80
     float rs_max = 0.f;
+    float e_half = 0.f;      // first probability of the pair being formed
+    float x_next;            // exponent of the next score, prepared one step ahead
 
     // operands of the 32-key half H of the K tile in stage ST
 #define PKV_LOAD_KA(ST, H)                                                               \
@@ -244,24 +246,36 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         va[kk][db] = *reinterpret_cast<const bf16x8*>(                                   \
             smem + NS * kStageK + (ST) * kStageV + db * 32 * 128 + vaddr[2 * (H) + kk]);
 
-    // The softmax of a sub-step is cut into pairs of scores (one packed bf16
-    // conversion each): pair PI of column block CB of score buffer S whose first
-    // key is T0.  p = exp2(s c2 - ref) with the reference of the column block;
-    // masked keys give exp2(-inf) = 0.
-#define PKV_SM_PAIR(S, CB, PI, T0, MASK)                                                 \
+    // The softmax of a sub-step goes one score per MFMA.  p = exp2(s c2 - ref) with the
+    // reference of the column block; masked keys give exp2(-inf) = 0.  PKV_SM_PREP
+    // forms the exponent of element R of column block CB of score buffer S (first
+    // key T0); PKV_SM_STEP turns the exponent prepared one step earlier into the
+    // probability of element (CB, R), and prepares the exponent of the next element
+    // in between, so that nothing waits on the transcendental unit.  The empty asm
+    // statements pin the results where they are computed: without them the compiler
+    // sinks the arithmetic towards its uses, away from the MFMAs it should hide under.
+#define PKV_SM_PREP(S, CB, R, T0, MASK)                                                  \
     {                                                                                    \
-        float x0_ = S[CB][2 * (PI)], x1_ = S[CB][2 * (PI) + 1];                          \
+        float x_ = S[CB][R];                                                             \
         if (MASK) {                                                                      \
-            const int key_ = (T0) + 16 * ((PI) / 4) + 8 * hh + (2 * (PI)) % 8;           \
-            if (key_ > limit[CB]) x0_ = -INFINITY;                                       \
-            if (key_ + 1 > limit[CB]) x1_ = -INFINITY;                                   \
+            const int key_ = (T0) + 16 * ((R) / 8) + 8 * hh + (R) % 8;                   \
+            if (key_ > limit[CB]) x_ = -INFINITY;                                        \
         }                                                                                \
-        const float e0_ = __builtin_amdgcn_exp2f(x0_ * c2 - msc[CB]);                    \
-        const float e1_ = __builtin_amdgcn_exp2f(x1_ * c2 - msc[CB]);                    \
-        rs[CB] += e0_;                                                                   \
-        rs[CB] += e1_;                                                                   \
-        pb[(PI) / 4][CB][(2 * (PI)) % 8] = (bf16_t)e0_;                                  \
-        pb[(PI) / 4][CB][(2 * (PI)) % 8 + 1] = (bf16_t)e1_;                              \
+        x_next = x_ * c2 - msc[CB];                                                      \
+    }
+#define PKV_SM_STEP(CB, R, SN, CBN, RN, T0N, MASK)                                       \
+    {                                                                                    \
+        const float e_ = __builtin_amdgcn_exp2f(x_next);                                 \
+        PKV_SM_PREP(SN, CBN, RN, T0N, MASK)                                              \
+        rs[CB] += e_;                                                                    \
+        if ((R) % 2 == 0) {                                                              \
+            e_half = e_;                                                                 \
+            asm volatile("" : "+v"(rs[CB]), "+v"(e_half), "+v"(x_next));                 \
+        } else {                                                                         \
+            pb[(R) / 8][CB][(R) % 8 - 1] = (bf16_t)e_half;                               \
+            pb[(R) / 8][CB][(R) % 8] = (bf16_t)e_;                                       \
+            asm volatile("" : "+v"(rs[CB]), "+v"(pb[(R) / 8][CB]), "+v"(x_next));        \
+        }                                                                                \
     }
 
     // The reference maximum m_run of a column is NOT the running maximum: it is the
@@ -285,6 +299,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     // four pairs of P(u), column block 0, were formed at the end of sub-step u-1.
     // 32 MFMAs, each pair of them followed by one softmax pair, so that the VALU
     // work is spread evenly under the matrix pipe:
+    // (one score after each MFMA):
     //    MFMA  1-16  S^T(u+1)            | P(u): block 0 pairs 4-7, block 1 pairs 0-3
     //    MFMA 17-24  O^T += V^T P^T, b.0 | P(u): block 1 pairs 4-7
     //    MFMA 25-32  O^T += V^T P^T, b.1 | P(u+1): block 0 pairs 0-3
@@ -294,40 +309,36 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         PKV_DMA_PAIR(DI, SDK, SDV)                                                       \
         __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_LOAD_VA(VST, VH)                                                             \
-        {                                                                                \
+        _Pragma("unroll") for (int i_ = 0; i_ < 16; ++i_) {                              \
             const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,                   \
                                0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};                  \
-            NXT[0] = mfma32(ka[0], qreg[0][0], z_);                                      \
-            NXT[1] = mfma32(ka[0], qreg[1][0], z_);                                      \
-        }                                                                                \
-        PKV_SM_PAIR(CUR, 0, 4, T0, MASK)                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                               \
-        _Pragma("unroll") for (int kc = 1; kc < KC; ++kc) {                              \
-            NXT[0] = mfma32(ka[kc], qreg[0][kc], NXT[0]);                                \
-            NXT[1] = mfma32(ka[kc], qreg[1][kc], NXT[1]);                                \
-            if (kc < 4) { PKV_SM_PAIR(CUR, 0, 4 + kc, T0, MASK) }                        \
-            else { PKV_SM_PAIR(CUR, 1, kc - 4, T0, MASK) }                               \
+            const int kc_ = i_ >> 1, cbm_ = i_ & 1;                                      \
+            NXT[cbm_] = mfma32(ka[kc_], qreg[cbm_][kc_], kc_ == 0 ? z_ : NXT[cbm_]);     \
+            if (i_ < 7) { PKV_SM_STEP(0, 8 + i_, CUR, 0, 9 + i_, T0, MASK) }             \
+            else if (i_ == 7) { PKV_SM_STEP(0, 15, CUR, 1, 0, T0, MASK) }                \
+            else { PKV_SM_STEP(1, i_ - 8, CUR, 1, i_ - 7, T0, MASK) }                    \
             __builtin_amdgcn_sched_barrier(0);                                           \
+            if (i_ == 7) {                                                               \
+                PKV_ACC(0)                                                               \
+                __builtin_amdgcn_sched_barrier(0);                                       \
+            }                                                                            \
         }                                                                                \
-        PKV_ACC(0)                                                                       \
-        __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_DMA_PAIR((DI) + 1, SDK, SDV)                                                 \
         __builtin_amdgcn_sched_barrier(0);                                               \
         PKV_LOAD_KA(KST, KH)                                                             \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                               \
-            const int kk_ = i_ >> 1, db_ = 2 * (i_ & 1);                                 \
+        _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                               \
+            const int kk_ = i_ >> 2, db_ = i_ & 3;                                       \
             o_acc[db_][0] = mfma32(va[kk_][db_], pb[kk_][0], o_acc[db_][0]);             \
-            o_acc[db_ + 1][0] = mfma32(va[kk_][db_ + 1], pb[kk_][0], o_acc[db_ + 1][0]); \
-            PKV_SM_PAIR(CUR, 1, 4 + i_, T0, MASK)                                        \
+            if (i_ < 7) { PKV_SM_STEP(1, 8 + i_, CUR, 1, 9 + i_, T0, MASK) }             \
+            else { PKV_SM_STEP(1, 15, NXT, 0, 0, (T0) + 32, MASK) }                      \
             __builtin_amdgcn_sched_barrier(0);                                           \
         }                                                                                \
         PKV_ACC(1)                                                                       \
         __builtin_amdgcn_sched_barrier(0);                                               \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                               \
-            const int kk_ = i_ >> 1, db_ = 2 * (i_ & 1);                                 \
+        _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                               \
+            const int kk_ = i_ >> 2, db_ = i_ & 3;                                       \
             o_acc[db_][1] = mfma32(va[kk_][db_], pb[kk_][1], o_acc[db_][1]);             \
-            o_acc[db_ + 1][1] = mfma32(va[kk_][db_ + 1], pb[kk_][1], o_acc[db_ + 1][1]); \
-            PKV_SM_PAIR(NXT, 0, i_, (T0) + 32, MASK)                                     \
+            PKV_SM_STEP(0, i_, NXT, 0, 1 + i_, (T0) + 32, MASK)                          \
             __builtin_amdgcn_sched_barrier(0);                                           \
         }                                                                                \
     }
@@ -375,8 +386,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         m_run[cb] = fmaxf(mx, __shfl_xor(mx, 32, 64));
         msc[cb] = (m_run[cb] == -INFINITY ? 0.f : m_run[cb]) * c2;
     }
+    PKV_SM_PREP(s_a, 0, 0, 0, true)
 #pragma unroll
-    for (int pi = 0; pi < 4; ++pi) PKV_SM_PAIR(s_a, 0, pi, 0, true)
+    for (int r = 0; r < 8; ++r) PKV_SM_STEP(0, r, s_a, 0, r + 1, 0, true)
     PKV_DMA_K(2, 2)
     PKV_DMA_V(1, 1)
 
@@ -404,7 +416,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 #undef PKV_DMA_PAIR
 #undef PKV_LOAD_KA
 #undef PKV_LOAD_VA
-#undef PKV_SM_PAIR
+#undef PKV_SM_PREP
+#undef PKV_SM_STEP
 #undef PKV_ACC
 #undef PKV_SUBSTEP
 #undef PKV_TILE
@@ -443,6 +456,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 }  // namespace
 
 pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
+    // every workgroup reports through p.flags; the operands must all be there
+    if (!p.q || !p.k || !p.vt || !p.row_pos || !p.out || !p.flags) return PKV_ERR_NULL;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dma128_kernel),
