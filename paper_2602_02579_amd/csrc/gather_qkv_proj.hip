@@ -239,7 +239,10 @@ bool mfma_proj_supported(const pkv_layer_cfg& cfg) {
 
 size_t gather_qkv_proj_ws_bytes(const pkv_layer_cfg& cfg, int64_t m) {
     if (!mfma_proj_supported(cfg)) return 0;
-    return (size_t)m * (cfg.head_dim / 2) * sizeof(float2);
+    size_t b = (size_t)m * (cfg.head_dim / 2) * sizeof(float2);
+    b = (b + 255) & ~(size_t)255;
+    if (proj_dma128_supported(cfg, m)) b += proj_dma128_partial_bytes(cfg, m);
+    return b;
 }
 
 pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
@@ -271,6 +274,8 @@ pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
             p.tile_begin[1] = tq;
             p.tile_begin[2] = tq + tkv;
             p.tile_begin[3] = tq + 2 * tkv;
+            const size_t cs_bytes = ((size_t)m * half * sizeof(float2) + 255) & ~(size_t)255;
+            p.partial = reinterpret_cast<float*>((unsigned char*)ws + cs_bytes);
             return launch_proj_dma128(p, st);
         }
         // column tiles: only the matrices whose outputs were asked for

@@ -23,6 +23,11 @@
 // Tiles are numbered so that each XCD (workgroup id mod 8) works through its own
 // contiguous run of tiles, 8 token tiles deep, and its L2 sees few distinct
 // operand panels at a time.
+//
+// A launch with few rows (the user-query projection of the scoring stage: 128 rows,
+// 16 tiles) cannot fill 256 CUs with tiles alone, so its contraction is split: every
+// split writes fp32 partial tiles, and a second small kernel adds them in a fixed
+// order, rotates and rounds (deterministic: no atomics).
 #include "proj_common.h"
 
 namespace pkv {
@@ -38,6 +43,7 @@ constexpr int kOperandBytes = T * kRowBytes;     // 16 KB: 256 rows of one opera
 constexpr int kStageBytes = 2 * kOperandBytes;   // token rows, then feature rows
 constexpr int kLdsBytes = NS * kStageBytes;      // 160 KB, all of a CU's LDS
 constexpr int kEpiStride = 272;                  // bytes per token of the store staging
+constexpr int kEpiStrideF32 = 528;               // same for fp32 partial tiles (32 tokens)
 constexpr int kGroup = 8;                        // token tiles per group
 
 // 16 bytes per lane from global memory straight into LDS: lane i of the wave
@@ -66,8 +72,10 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
     const int wt = wave >> 1, wf = wave & 1;
 
     // ---- which tile --------------------------------------------------------------
-    const int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (logical >= n_tiles) return;
+    int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (logical >= n_tiles * p.n_ksplit) return;
+    const int split = logical / n_tiles;
+    logical -= split * n_tiles;
     const int n_feat_tiles = p.tile_begin[3];
     const int per_group = kGroup * n_feat_tiles;
     const int group = logical / per_group;
@@ -85,6 +93,9 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
     const int heads_out = mat == 0 ? p.hq : p.hkv;
     const int row0 = tok_tile * T;
 
+    const int n_k = p.hid / BK / p.n_ksplit;   // stages of this split; >= NS (launcher)
+    const int k_begin = split * n_k * BK;
+
     // ---- fill side: wave w, instruction j covers rows 16 (4w + j) .. + 16 ------------
     const int sw = (lane & 3) ^ ((lane >> 4) & 3);   // global chunk that lands at lane & 3
     const bf16_t* xptr[4];
@@ -94,8 +105,8 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
         const int r = (wave * 4 + j) * 16 + (lane >> 2);
         const int gr = min(row0 + r, p.m - 1);
         const int64_t src_row = p.row_idx ? p.row_idx[gr] : gr;
-        xptr[j] = p.hidden + src_row * p.hid + sw * 8;
-        wptr[j] = w + (int64_t)(feat0 + r) * p.hid + sw * 8;
+        xptr[j] = p.hidden + src_row * p.hid + k_begin + sw * 8;
+        wptr[j] = w + (int64_t)(feat0 + r) * p.hid + k_begin + sw * 8;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(lds0 + wave * 4 * 1024);
@@ -156,7 +167,6 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
         }
     };
 
-    const int n_k = p.hid / BK;   // >= NS, checked by the launcher
     // prologue: stages 0 .. NS-3 and the first half of stage NS-2 in flight
 #pragma unroll
     for (int s = 0; s < NS - 2; ++s)
@@ -193,6 +203,38 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
     // ---- epilogue: rotate pairs in registers, round once, stage, store 16 B per lane ----
     if (out == nullptr) return;   // uniform over the workgroup
     __syncthreads();              // LDS stages are free
+    if (p.n_ksplit > 1) {
+        // fp32 partial tile of this split, staged so that a lane stores 16 B and a
+        // row 512 B: partial[split][row][256 ft + 128 wf + feature]
+        unsigned char* epf = smem + wave * (32 * kEpiStrideF32);
+        const int f_total = T * p.tile_begin[3];
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {
+            const int rbase = row0 + wt * 128 + tb * 32;
+            if (rbase >= p.m) break;   // wave-uniform
+            unsigned char* erow = epf + l32 * kEpiStrideF32;
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    f32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[fb][tb][4 * j + e];
+                    *reinterpret_cast<f32x4*>(erow + (fb * 32 + 8 * j + 4 * hh) * 4) = v;
+                }
+#pragma unroll
+            for (int it = 0; it < 16; ++it) {
+                const int idx = it * 64 + lane;
+                const int tok = idx >> 5, ch = idx & 31;
+                const int row = rbase + tok;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(epf + tok * kEpiStrideF32 + ch * 16);
+                if (row < p.m)
+                    *reinterpret_cast<f32x4*>(p.partial + ((int64_t)split * p.m + row) * f_total +
+                                              ft * T + wf * 128 + ch * 4) = v;
+            }
+        }
+        return;
+    }
     const int head = feat0 / D + wf;
     const bool rotate = mat != 2;
     unsigned char* epi = smem + wave * (64 * kEpiStride);
@@ -250,7 +292,60 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
     }
 }
 
+// adds the splits of the contraction in a fixed order, rotates, rounds once, stores.
+// One thread per (row, head slot, pair index i): elements i and i + 64 of the head.
+__global__ __launch_bounds__(256) void proj_splitk_finish_kernel(ProjParams p) {
+    const int f_total = T * p.tile_begin[3];
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = (int64_t)p.m * (f_total / 2);
+    if (idx >= total) return;
+    const int i = (int)(idx % (D / 2));
+    const int hs = (int)((idx / (D / 2)) % (f_total / D));   // head slot over Q | K | V
+    const int row = (int)(idx / ((int64_t)(D / 2) * (f_total / D)));
+    const int ft = hs / 2;
+    int mat = 0;
+    if (ft >= p.tile_begin[1]) mat = 1;
+    if (ft >= p.tile_begin[2]) mat = 2;
+    bf16_t* out = p.out[mat];
+    if (out == nullptr) return;
+    const int head = (ft - p.tile_begin[mat]) * 2 + (hs & 1);
+    const int heads_out = mat == 0 ? p.hq : p.hkv;
+    float a = 0.f, b = 0.f;
+    for (int s = 0; s < p.n_ksplit; ++s) {
+        const float* src = p.partial + ((int64_t)s * p.m + row) * f_total + hs * D + i;
+        a += src[0];
+        b += src[D / 2];
+    }
+    if (mat != 2) {
+        const float2 t = p.cs[(int64_t)row * (D / 2) + i];
+        const float ra = a * t.x - b * t.y;
+        const float rb = b * t.x + a * t.y;
+        a = ra;
+        b = rb;
+    }
+    bf16_t* o = out + ((int64_t)row * heads_out + head) * D + i;
+    o[0] = (bf16_t)a;
+    o[D / 2] = (bf16_t)b;
+}
+
+// splits of the contraction for a launch of n_tiles tiles over n_k stages: the largest
+// power of two that keeps the launch within ~256 workgroups and a split >= NS stages
+int plan_ksplit(int64_t n_tiles, int n_k) {
+    int ks = 1;
+    while (ks < 16 && n_tiles * (ks * 2) <= 256 && n_k % (ks * 2) == 0 && n_k / (ks * 2) >= NS)
+        ks *= 2;
+    return ks;
+}
+
 }  // namespace
+
+size_t proj_dma128_partial_bytes(const pkv_layer_cfg& cfg, int64_t m) {
+    // n_ksplit * (features of the launch) <= 256 * 256 / (token tiles): see plan_ksplit
+    const int64_t n_tok_tiles = ceil_div(m, T);
+    if (n_tok_tiles > 128) return 0;
+    (void)cfg;
+    return (size_t)m * (size_t)(T * 256 / n_tok_tiles) * sizeof(float);
+}
 
 bool proj_dma128_supported(const pkv_layer_cfg& cfg, int64_t m) {
     return cfg.dtype == PKV_BF16 && cfg.head_dim == D && cfg.hidden % BK == 0 &&
@@ -271,9 +366,17 @@ pkv_status launch_proj_dma128(const ProjParams& p, hipStream_t st) {
     const int64_t n_tiles = (int64_t)n_tok_tiles * p.tile_begin[3];
     if (n_tiles == 0) return PKV_OK;
     if (n_tiles > (1 << 30)) return PKV_ERR_SHAPE;
-    const int per_xcd = (int)ceil_div(n_tiles, 8);
+    ProjParams q = p;
+    q.n_ksplit = plan_ksplit(n_tiles, p.hid / BK);
+    if (q.n_ksplit > 1 && q.partial == nullptr) return PKV_ERR_WORKSPACE;
+    const int per_xcd = (int)ceil_div(n_tiles * q.n_ksplit, 8);
     hipLaunchKernelGGL(qkv_proj_dma128_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256),
-                       kLdsBytes, st, p, n_tok_tiles, (int)n_tiles, per_xcd);
+                       kLdsBytes, st, q, n_tok_tiles, (int)n_tiles, per_xcd);
+    if (q.n_ksplit > 1) {
+        const int64_t total = (int64_t)p.m * (T * p.tile_begin[3] / 2);
+        hipLaunchKernelGGL(proj_splitk_finish_kernel, dim3((unsigned)ceil_div(total, 256)),
+                           dim3(256), 0, st, q);
+    }
     return launch_status();
 }
 

@@ -13,6 +13,8 @@ struct ProjParams {
     const float2* cs;     // [m, D/2] (cos, sin) of every output row's position
     int m, hid, hq, hkv;
     int tile_begin[4];    // first feature tile of Q, K, V, end
+    float* partial;       // [n_ksplit, m, 256 * tile_begin[3]] fp32, used when n_ksplit > 1
+    int n_ksplit;         // splits of the contraction (1 = none)
 };
 
 // head_dim 128, 256 x 256 output tiles, operands brought into LDS by direct
@@ -20,6 +22,9 @@ struct ProjParams {
 // 256 output features (two heads).
 constexpr int kProjDmaTile = 256;
 bool proj_dma128_supported(const pkv_layer_cfg& cfg, int64_t m);
+// bytes of fp32 partials that a launch with m rows may need (0 when the launch is large
+// enough to fill the chip without splitting the contraction)
+size_t proj_dma128_partial_bytes(const pkv_layer_cfg& cfg, int64_t m);
 pkv_status launch_proj_dma128(const ProjParams& p, hipStream_t st);
 
 }  // namespace pkv

@@ -68,6 +68,7 @@ class SelectiveRecompute:
             api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, self.lc, n, qn),
             api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, self.lc, n + qn, self.m),
             api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, self.lc, 0, self.m),
+            api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, self.lc, 0, qn),
             256)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
 
