@@ -129,20 +129,34 @@ __global__ __launch_bounds__(256) void score_colsum_generic(
 // the kv heads in a fixed order, so the score is deterministic.
 // ---------------------------------------------------------------------------
 
-__global__ void merge_lse_kernel(const float* __restrict__ part_ml,
-                                 float* __restrict__ lse2, int ncol, int n_splits,
-                                 float scale_log2) {
-    const int col = blockIdx.x * blockDim.x + threadIdx.x;
-    if (col >= ncol) return;
-    float mx = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, part_ml[((int64_t)s * ncol + col) * 2]);
-    float sum = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float m = part_ml[((int64_t)s * ncol + col) * 2];
-        const float l = part_ml[((int64_t)s * ncol + col) * 2 + 1];
-        if (m != -INFINITY) sum += l * exp2f((m - mx) * scale_log2);
+// 64 columns per block; the four waves fold every fourth split each, then meet in LDS
+__global__ __launch_bounds__(256) void merge_lse_kernel(const float* __restrict__ part_ml,
+                                                        float* __restrict__ lse2, int ncol,
+                                                        int n_splits, float scale_log2) {
+    __shared__ float s_m[4][64], s_l[4][64];
+    const int c = threadIdx.x & 63, part = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + c;
+    float mx = -INFINITY, sum = 0.f;
+    if (col < ncol) {
+        for (int s = part; s < n_splits; s += 4) {
+            const float2 ml = *reinterpret_cast<const float2*>(part_ml + ((int64_t)s * ncol + col) * 2);
+            if (ml.x == -INFINITY) continue;
+            const float mn = fmaxf(mx, ml.x);
+            sum = sum * exp2f((mx - mn) * scale_log2) + ml.y * exp2f((ml.x - mn) * scale_log2);
+            mx = mn;
+        }
     }
-    lse2[col] = mx * scale_log2 + log2f(sum);
+    s_m[part][c] = mx;
+    s_l[part][c] = sum;
+    __syncthreads();
+    if (part == 0 && col < ncol) {
+        float m = -INFINITY;
+        for (int q = 0; q < 4; ++q) m = fmaxf(m, s_m[q][c]);
+        float l = 0.f;
+        for (int q = 0; q < 4; ++q)
+            if (s_m[q][c] != -INFINITY) l += s_l[q][c] * exp2f((s_m[q][c] - m) * scale_log2);
+        lse2[col] = m * scale_log2 + log2f(l);
+    }
 }
 
 template <int D>
@@ -173,13 +187,22 @@ __global__ __launch_bounds__(256) void score_colsum_mfma(
         for (int r = 0; r < 16; ++r) acc[kb][r] = 0.f;
 
     const int ncol_g = nq * group;
-    for (int c0 = 0; c0 < ncol_g; c0 += 32) {
-        const int col = c0 + l32;
-        const bool valid = col < ncol_g;
-        const int qi = valid ? col / group : 0;
-        const int h = g * group + (valid ? col % group : 0);
+    // operands of column block c0 (clamped: lanes past the last column re-read it and
+    // are switched off through an infinite normaliser)
+    bf16x8 b[KC], bn[KC];
+    float norm, norm_n;
+    auto load_cols = [&](int c0, bf16x8* dst, float* nrm) {
+        const int col = min(c0 + l32, ncol_g - 1);
+        const int qi = col / group;
+        const int h = g * group + col % group;
         const bf16_t* qp = q + ((int64_t)qi * hq + h) * D + hh * 8;
-        const float norm = valid ? lse2[(int64_t)qi * hq + h] : INFINITY;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) dst[kc] = *reinterpret_cast<const bf16x8*>(qp + kc * 16);
+        *nrm = c0 + l32 < ncol_g ? lse2[(int64_t)qi * hq + h] : INFINITY;
+    };
+    load_cols(0, b, &norm);
+    for (int c0 = 0; c0 < ncol_g; c0 += 32) {
+        load_cols(min(c0 + 32, ncol_g - 1), bn, &norm_n);   // next block, in flight during the MFMAs
         f32x16 s[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -187,15 +210,17 @@ __global__ __launch_bounds__(256) void score_colsum_mfma(
             for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) {
-            const bf16x8 b = *reinterpret_cast<const bf16x8*>(qp + kc * 16);
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][kc], b, s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][kc], b, s[1], 0, 0, 0);
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][kc], b[kc], s[0], 0, 0, 0);
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][kc], b[kc], s[1], 0, 0, 0);
         }
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                acc[kb][r] += exp2f(s[kb][r] * scale_log2 - norm);
+                acc[kb][r] += __builtin_amdgcn_exp2f(s[kb][r] * scale_log2 - norm);
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) b[kc] = bn[kc];
+        norm = norm_n;
     }
     // sum over the 32 columns held by the lanes of each half
 #pragma unroll
@@ -288,7 +313,7 @@ pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
         pkv_status stt = launch_attn_lse_partials(cfg, q, k, nq, n_ctx, scale, sp.n_splits,
                                                   sp.split_len, part_ml, st);
         if (stt != PKV_OK) return stt;
-        hipLaunchKernelGGL(merge_lse_kernel, dim3((unsigned)ceil_div(ncol, 256)), dim3(256),
+        hipLaunchKernelGGL(merge_lse_kernel, dim3((unsigned)ceil_div(ncol, 64)), dim3(256),
                            0, st, part_ml, lse2, ncol, sp.n_splits, scale_log2);
         const dim3 grid((unsigned)ceil_div(n_ctx, 256), (unsigned)hkv);
         if (d == 128) {

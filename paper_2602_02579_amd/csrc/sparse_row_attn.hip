@@ -146,13 +146,16 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
 
     // work item: kv head (fastest, so that a head stays on one XCD when
     // hkv == 8), key split, row tile (heaviest tiles first)
-    int wg = blockIdx.x;
+    // normally one work item per workgroup; the repair pass (p.flags set) is launched
+    // with a small grid whose workgroups walk over all items and skip the unmarked ones
+    for (int wg0 = blockIdx.x; wg0 < p.n_tiles * p.n_splits * p.hkv; wg0 += gridDim.x) {
+    int wg = wg0;
     const int g = wg % p.hkv;
     wg /= p.hkv;
     const int split = wg % p.n_splits;
     const int tile = p.n_tiles - 1 - wg / p.n_splits;
     // repair pass: only the tiles that the pipelined kernel marked
-    if (p.flags && p.flags[tile * p.hkv + g] == 0) return;
+    if (p.flags && p.flags[tile * p.hkv + g] == 0) continue;
 
     // ---- my two columns ----------------------------------------------------
     int limit[2], row[2], head[2];
@@ -377,6 +380,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
                 p.lse[colg] = m_run[cb] * p.scale + logf(l_run[cb]);
         }
     }
+    __syncthreads();   // LDS and s_red are reused by the next work item
+    }
 }
 
 // V [n_keys, hkv, D] -> V^T [hkv, D, n_pad], zero for keys >= n_keys.
@@ -445,7 +450,8 @@ pkv_status launch_attn_mfma(const AttnParams& p, hipStream_t st) {
             return PKV_ERR_LAUNCH;
         configured = true;
     }
-    const int64_t grid = (int64_t)p.n_tiles * p.n_splits * p.hkv;
+    int64_t grid = (int64_t)p.n_tiles * p.n_splits * p.hkv;
+    if (p.flags && grid > 256) grid = 256;   // repair pass: one resident workgroup per CU
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kAttnThreads), AttnLds<D>::bytes,
                        st, p);
     return launch_status();

@@ -4,7 +4,19 @@
 // indices"; Sec. 4.3: the set is chosen once and used by every layer.)
 //
 // One workgroup of 1024 lanes (16 waves).  The score vector is small (128 KB
-// at 32k context) and stays in L2, so the kernel is latency-bound:
+// at 32k context) and stays in L2, so the kernel is latency-bound.
+//
+// Up to 64 scores per lane (n <= 65536) the keys live in registers, each lane
+// owning a contiguous run of indices (topk_bisect_kernel):
+//   1. the key tau of the k-th largest score is built bit by bit from the top:
+//      32 rounds of "how many keys are >= candidate", each a compare-and-count
+//      over the lane's registers, a DPP row reduction and one barrier - no
+//      atomics, so the skewed digit distribution of real scores (all in two or
+//      three binades) costs nothing;
+//   2. two block-wide exclusive scans (keys > tau, keys == tau) give every
+//      lane the output offset of its run; equal keys are taken in index order
+//      until the need is met - the lower-index tie rule.
+// Longer vectors use the radix kernel below:
 //   1. radix select, 4 passes of 8 bits over order-preserving uint32 keys,
 //      finds the key tau of the k-th largest score and how many scores equal
 //      to tau are still needed;
@@ -141,11 +153,132 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(
     }
 }
 
+// sum over the wave of a small per-lane count, returned wave-uniform
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+    // inclusive scan inside each row of 16 lanes (row_shr 1, 2, 4, 8; lanes shifted in
+    // from outside the row read 0), then the four row totals
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 15) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 31) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 47) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+template <int ITEMS>
+__global__ __launch_bounds__(kThreads) void topk_bisect_kernel(
+    const float* __restrict__ score, int n, int k, int32_t* __restrict__ idx_out) {
+    __shared__ uint32_t s_wave[2][kWaves];
+    __shared__ uint32_t s_scan[2][kWaves];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    // lane tid owns indices [tid * ITEMS, tid * ITEMS + ITEMS); indices >= n get key 0,
+    // which is below the key of every float (order_key(-inf) = 0x007fffff)
+    uint32_t key[ITEMS];
+    const int base = tid * ITEMS;
+#pragma unroll
+    for (int j = 0; j < ITEMS; j += 4) {
+        if (base + j + 3 < n) {
+            const float4 v = *reinterpret_cast<const float4*>(score + base + j);
+            key[j] = order_key(v.x);
+            key[j + 1] = order_key(v.y);
+            key[j + 2] = order_key(v.z);
+            key[j + 3] = order_key(v.w);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                key[j + e] = base + j + e < n ? order_key(score[base + j + e]) : 0u;
+        }
+    }
+
+    // block-wide count of keys for which PRED holds (one barrier; s_wave is double
+    // buffered so that a fast wave cannot overwrite what a slow one still reads)
+    int round = 0;
+#define PKV_BLOCK_COUNT(PRED, RESULT)                                                    \
+    {                                                                                    \
+        uint32_t c_ = 0;                                                                 \
+        _Pragma("unroll") for (int j = 0; j < ITEMS; ++j) c_ += (PRED) ? 1u : 0u;        \
+        c_ = wave_sum(c_);                                                               \
+        if (lane == 0) s_wave[round & 1][wave] = c_;                                     \
+        __syncthreads();                                                                 \
+        uint32_t t_ = 0;                                                                 \
+        _Pragma("unroll") for (int w = 0; w < kWaves; ++w) t_ += s_wave[round & 1][w];   \
+        RESULT = t_;                                                                     \
+        ++round;                                                                         \
+    }
+
+    // ---- 1. tau = the k-th largest key, bit by bit ---------------------------------
+    uint32_t tau = 0;
+    for (int b = 31; b >= 0; --b) {
+        const uint32_t cand = tau | (1u << b);
+        uint32_t cnt;
+        PKV_BLOCK_COUNT(key[j] >= cand, cnt)
+        if (cnt >= (uint32_t)k) tau = cand;
+    }
+    uint32_t n_gt;
+    PKV_BLOCK_COUNT(key[j] > tau, n_gt)
+    const uint32_t need = (uint32_t)k - n_gt;   // keys == tau still to take
+#undef PKV_BLOCK_COUNT
+
+    // ---- 2. output offsets: exclusive scans over the lanes in index order -------------
+    uint32_t my_gt = 0, my_eq = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        my_gt += key[j] > tau ? 1u : 0u;
+        my_eq += key[j] == tau ? 1u : 0u;
+    }
+    uint32_t in_gt = my_gt, in_eq = my_eq;   // inclusive scans inside the wave
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t og = __shfl_up(in_gt, d, 64), oe = __shfl_up(in_eq, d, 64);
+        if (lane >= d) {
+            in_gt += og;
+            in_eq += oe;
+        }
+    }
+    if (lane == 63) {
+        s_scan[0][wave] = in_gt;
+        s_scan[1][wave] = in_eq;
+    }
+    __syncthreads();
+    uint32_t gt_before = in_gt - my_gt, eq_before = in_eq - my_eq;
+    for (int w = 0; w < wave; ++w) {
+        gt_before += s_scan[0][w];
+        eq_before += s_scan[1][w];
+    }
+    // equal keys at lower indices are taken first, until `need` of them are
+    uint32_t out = gt_before + (eq_before < need ? eq_before : need);
+    uint32_t eq_seen = eq_before;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const bool is_eq = key[j] == tau;
+        const bool take = key[j] > tau || (is_eq && eq_seen < need);
+        if (take) idx_out[out++] = base + j;
+        eq_seen += is_eq ? 1u : 0u;
+    }
+}
+
 }  // namespace
 
 pkv_status launch_topk_select(const float* score, int64_t n, int64_t k,
                               int32_t* idx_out, hipStream_t st) {
     if (n == 0 || k == 0) return PKV_OK;
+    // the register kernels read 16 bytes at a time
+    const bool aligned = (reinterpret_cast<uintptr_t>(score) & 15) == 0;
+    if (aligned && n <= 32 * kThreads) {
+        hipLaunchKernelGGL(topk_bisect_kernel<32>, dim3(1), dim3(kThreads), 0, st, score,
+                           (int)n, (int)k, idx_out);
+        return launch_status();
+    }
+    if (aligned && n <= 64 * kThreads) {
+        hipLaunchKernelGGL(topk_bisect_kernel<64>, dim3(1), dim3(kThreads), 0, st, score,
+                           (int)n, (int)k, idx_out);
+        return launch_status();
+    }
     hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kThreads), 0, st, score,
                        (int)n, (int)k, idx_out);
     return launch_status();

@@ -131,10 +131,19 @@ def run_topk(score_np, k, device):
 
 @pytest.mark.parametrize("n,k", [(1, 1), (63, 10), (64, 64), (1000, 0), (1000, 1000),
                                  (1024, 204), (32768, 6553), (131072, 26214),
-                                 (100003, 99999), (65, 1)])
+                                 (100003, 99999), (65, 1), (50000, 12345), (65536, 100),
+                                 (32769, 32768), (40001, 1)])
 def test_topk_matches_oracle(gpu_device, n, k):
     s = np.random.default_rng(n + k).random(n).astype(np.float32) / n
     assert np.array_equal(run_topk(s, k, gpu_device), O.topk_select(s, k))
+
+
+def test_topk_score_pointer_not_16_byte_aligned(gpu_device):
+    s = np.random.default_rng(77).random(20001).astype(np.float32)
+    full = torch.from_numpy(s).to(gpu_device)
+    out = torch.empty(5000, dtype=torch.int32, device=gpu_device)
+    api.pkv_topk_select(full[1:], 5000, out)      # data pointer offset by 4 bytes
+    assert np.array_equal(out.cpu().numpy(), O.topk_select(s[1:], 5000))
 
 
 def test_topk_ties_negative_values_and_zeros(gpu_device):
