@@ -160,17 +160,21 @@ def attn_flops(rows_pos: np.ndarray, hq: int, d: int) -> float:
     return 4.0 * hq * d * float((rows_pos.astype(np.int64) + 1).sum())
 
 
-def time_calls(fn, reps):
+def time_calls(fn, reps, batch=10):
+    """Seconds per call: the median over `reps` batches of `batch` back-to-back calls
+    between one pair of events (a single call between events would mostly measure the
+    launch gap for the 10-30 us kernels)."""
     s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     fn()
     torch.cuda.synchronize()
     ts = []
     for _ in range(reps):
         s.record()
-        fn()
+        for _ in range(batch):
+            fn()
         e.record()
         e.synchronize()
-        ts.append(s.elapsed_time(e) * 1e-3)
+        ts.append(s.elapsed_time(e) * 1e-3 / batch)
     return float(np.median(ts))
 
 

@@ -35,17 +35,16 @@ __global__ __launch_bounds__(256) void rope_restore_kernel(
         const int64_t t = w / chunks;
         const int i0 = (int)(w - t * chunks) * V;
         const double p = pos ? (double)pos[t] : (double)(pos_base + t);
-        float sn[V], cs[V];
-#pragma unroll
-        for (int j = 0; j < V; ++j) rope_sincos(p, tab.inv_freq[i0 + j], &sn[j], &cs[j]);
         const T* src = k_in + t * (int64_t)n_heads * head_dim + i0;
         T* dst = k_out + t * (int64_t)n_heads * head_dim + i0;
         // heads in batches of HB: all loads of a batch are issued before its
-        // stores, which keeps several 16-byte requests in flight per lane
-        // without assuming that k_in and k_out do not alias (in place is allowed)
-        constexpr int HB = 4;
-        for (int h0 = 0; h0 < n_heads; h0 += HB) {
-            vec_t a[HB], b[HB];
+        // stores, which keeps many 16-byte requests in flight per lane without
+        // assuming that k_in and k_out do not alias (in place is allowed); the
+        // first batch is requested before the sines and cosines are worked out,
+        // so that arithmetic runs under the memory latency
+        constexpr int HB = 8;
+        vec_t a[HB], b[HB];
+        auto load_batch = [&](int h0) {
 #pragma unroll
             for (int u = 0; u < HB; ++u) {
                 if (h0 + u < n_heads) {
@@ -53,6 +52,13 @@ __global__ __launch_bounds__(256) void rope_restore_kernel(
                     b[u] = *reinterpret_cast<const vec_t*>(src + (h0 + u) * head_dim + half);
                 }
             }
+        };
+        load_batch(0);
+        float sn[V], cs[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) rope_sincos(p, tab.inv_freq[i0 + j], &sn[j], &cs[j]);
+        for (int h0 = 0; h0 < n_heads; h0 += HB) {
+            if (h0 > 0) load_batch(h0);
 #pragma unroll
             for (int u = 0; u < HB; ++u) {
                 if (h0 + u < n_heads) {
