@@ -18,7 +18,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libpkv.so")
 
-SOURCES = ["pkv_api.hip", "rope_restore.hip", "query_score.hip",
+SOURCES = ["pkv_api.hip", "rope_restore.hip", "query_score.hip", "query_score_dma.hip",
            "topk_select.hip", "gather_qkv_proj.hip", "gather_qkv_proj_dma.hip",
            "scatter_kv.hip",
            "sparse_row_attn.hip", "sparse_row_attn_dma.hip"]

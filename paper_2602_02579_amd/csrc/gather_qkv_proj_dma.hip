@@ -151,12 +151,17 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
         for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
-    // 16 MFMAs of one contraction sub-step; one fill instruction goes out after every
+    // 16 MFMAs of one contraction sub-step.  One fill instruction goes out after every
     // fourth MFMA (half a stage per sub-step), so the memory pipeline sees a steady
-    // trickle instead of a burst that stalls the wave
-    auto mfma16 = [&](int slot, int fill_stage, int j0, int adv) {
+    // trickle instead of a burst that stalls the wave; the operands of the next
+    // sub-step (stage lstage, sub-step lks) are read from LDS in the same rhythm,
+    // two per four MFMAs, into the other register slot
+    auto mfma16 = [&](int slot, int fill_stage, int j0, int adv, int lstage, int lks) {
+        const unsigned char* sb = smem + lstage * kStageBytes;
 #pragma unroll
         for (int fb = 0; fb < 4; ++fb) {
+            fw[slot ^ 1][fb] = *reinterpret_cast<const bf16x8*>(sb + off_w[lks] + fb * 32 * kRowBytes);
+            fx[slot ^ 1][fb] = *reinterpret_cast<const bf16x8*>(sb + off_x[lks] + fb * 32 * kRowBytes);
 #pragma unroll
             for (int tb = 0; tb < 4; ++tb)
                 acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[slot][fb], fx[slot][tb],
@@ -188,14 +193,10 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
         const int st_next = st_cur + 1 == NS ? 0 : st_cur + 1;
         const int st_fill = st_cur == 0 ? NS - 1 : st_cur - 1;          // (t + NS - 1) mod NS
         const int st_fill_b = st_fill == 0 ? NS - 1 : st_fill - 1;      // (t + NS - 2) mod NS
-        load_frags(st_cur, 1, 1);
-        // second half of the fill of stage t + NS - 2 (its slot was freed one barrier ago)
-        mfma16(0, st_fill_b, 2, t + NS - 1 < n_k ? BK : 0);
+        mfma16(0, st_fill_b, 2, t + NS - 1 < n_k ? BK : 0, st_cur, 1);
         wait_vm<8 * (NS - 3)>();  // stage t+1 has landed; the younger ones stay in flight
         __syncthreads();          // ... for everyone; and everyone is done with stage t-1
-        load_frags(st_next, 0, 0);
-        // first half of the fill of stage t + NS - 1, into the slot of stage t-1
-        mfma16(1, st_fill, 0, t + NS < n_k ? BK : 0);
+        mfma16(1, st_fill, 0, t + NS < n_k ? BK : 0, st_next, 0);
         st_cur = st_next;
     }
     wait_vm<0>();                 // the ring's trailing fills must not land in the staging

@@ -11,7 +11,7 @@
 //   pass 1  lse per (query token, head) column;
 //   pass 2  per key, the sum over all columns of exp(s - lse), written once
 //           per key (no atomics, so the result is deterministic).
-#include "pkv_common.h"
+#include "score_common.h"
 
 namespace pkv {
 
@@ -242,15 +242,24 @@ __global__ __launch_bounds__(256) void score_colsum_mfma(
     }
 }
 
-__global__ void finish_score_kernel(const float* __restrict__ part_score,
-                                    float* __restrict__ score, int n_ctx, int hkv,
-                                    float inv_ncol, int accumulate) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= n_ctx) return;
+// 64 keys per block; the four waves add every fourth partial each (in order), then
+// meet in LDS in a fixed order: deterministic
+__global__ __launch_bounds__(256) void finish_score_kernel(const float* __restrict__ part_score,
+                                                           float* __restrict__ score, int n_ctx,
+                                                           int n_parts, float inv_ncol,
+                                                           int accumulate) {
+    __shared__ float s_part[4][64];
+    const int kx = threadIdx.x & 63, py = threadIdx.x >> 6;
+    const int t = blockIdx.x * 64 + kx;
     float s = 0.f;
-    for (int g = 0; g < hkv; ++g) s += part_score[(int64_t)g * n_ctx + t];
-    s *= inv_ncol;
-    score[t] = accumulate ? score[t] + s : s;
+    if (t < n_ctx)
+        for (int q = py; q < n_parts; q += 4) s += part_score[(int64_t)q * n_ctx + t];
+    s_part[py][kx] = s;
+    __syncthreads();
+    if (py == 0 && t < n_ctx) {
+        const float tot = ((s_part[0][kx] + s_part[1][kx]) + s_part[2][kx]) + s_part[3][kx];
+        score[t] = accumulate ? score[t] + tot * inv_ncol : tot * inv_ncol;
+    }
 }
 
 bool mfma_score_supported(const pkv_layer_cfg& cfg) {
@@ -289,6 +298,12 @@ pkv_status launch_attn_lse_partials(const pkv_layer_cfg& cfg, const void* q,
 size_t query_score_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_ctx, int64_t nq) {
     const size_t ncol = (size_t)(nq * cfg.n_q_heads);
     if (!mfma_score_supported(cfg)) return ncol * sizeof(float);
+    if (score_dma128_supported(cfg, n_ctx, nq)) {
+        const ScorePlan sp = plan_score_dma128(cfg, n_ctx, nq);
+        return align_up(ncol * sizeof(float)) +
+               align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)) +
+               align_up((size_t)sp.n_parts * n_ctx * sizeof(float));
+    }
     const SplitPlan sp = plan_splits(cfg, n_ctx, nq);
     return align_up(ncol * sizeof(float)) +
            align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)) +
@@ -302,6 +317,33 @@ pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
     float* lse = (float*)ws;
     const int ncol = (int)(nq * cfg.n_q_heads);
     const int hq = cfg.n_q_heads, hkv = cfg.n_kv_heads, d = cfg.head_dim;
+    if (mfma_score_supported(cfg) && score_dma128_supported(cfg, n_ctx, nq)) {
+        const ScorePlan sp = plan_score_dma128(cfg, n_ctx, nq);
+        unsigned char* base = (unsigned char*)ws;
+        float* lse2 = (float*)base;
+        float* part_ml = (float*)(base + align_up((size_t)ncol * sizeof(float)));
+        float* part_score = (float*)((unsigned char*)part_ml +
+                                     align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)));
+        ScoreParams sp_ = {};
+        sp_.q = (const bf16_t*)q;
+        sp_.k = (const bf16_t*)k;
+        sp_.part_ml = part_ml;
+        sp_.lse2 = lse2;
+        sp_.part_score = part_score;
+        sp_.nq = (int)nq; sp_.n_ctx = (int)n_ctx; sp_.hq = hq; sp_.hkv = hkv; sp_.group = hq / hkv;
+        sp_.n_cblk = sp.n_cblk; sp_.n_splits = sp.n_splits; sp_.split_len = sp.split_len;
+        sp_.scale_log2 = scale * 1.4426950408889634f;
+        pkv_status stt = launch_score_dma128(1, sp_, st);
+        if (stt != PKV_OK) return stt;
+        hipLaunchKernelGGL(merge_lse_kernel, dim3((unsigned)ceil_div(ncol, 64)), dim3(256),
+                           0, st, part_ml, lse2, ncol, sp.n_splits, sp_.scale_log2);
+        stt = launch_score_dma128(2, sp_, st);
+        if (stt != PKV_OK) return stt;
+        hipLaunchKernelGGL(finish_score_kernel, dim3((unsigned)ceil_div(n_ctx, 64)),
+                           dim3(256), 0, st, part_score, score, (int)n_ctx, sp.n_parts,
+                           1.0f / (float)ncol, accumulate);
+        return launch_status();
+    }
     if (mfma_score_supported(cfg)) {
         const SplitPlan sp = plan_splits(cfg, n_ctx, nq);
         unsigned char* base = (unsigned char*)ws;
@@ -325,7 +367,7 @@ pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
                                (const bf16_t*)q, (const bf16_t*)k, lse2, part_score,
                                (int)nq, (int)n_ctx, hq, hkv, hq / hkv, scale_log2);
         }
-        hipLaunchKernelGGL(finish_score_kernel, dim3((unsigned)ceil_div(n_ctx, 256)),
+        hipLaunchKernelGGL(finish_score_kernel, dim3((unsigned)ceil_div(n_ctx, 64)),
                            dim3(256), 0, st, part_score, score, (int)n_ctx, hkv,
                            1.0f / (float)ncol, accumulate);
         return launch_status();

@@ -147,7 +147,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
     // work item: kv head (fastest, so that a head stays on one XCD when
     // hkv == 8), key split, row tile (heaviest tiles first)
     // normally one work item per workgroup; the repair pass (p.flags set) is launched
-    // with a small grid whose workgroups walk over all items and skip the unmarked ones
+    // with a small grid whose workgroups walk over all items and skip the unmarked ones;
+    // the count of marked tiles sits behind the flags, and is zero almost always
+    if (p.flags && p.flags[p.n_tiles * p.hkv] == 0) return;
     for (int wg0 = blockIdx.x; wg0 < p.n_tiles * p.n_splits * p.hkv; wg0 += gridDim.x) {
     int wg = wg0;
     const int g = wg % p.hkv;
@@ -388,8 +390,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
 // 64 x 64 tiles through LDS; reads and writes are both 16-byte, coalesced.
 __global__ __launch_bounds__(256) void transpose_v_kernel(
     const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int n_keys, int n_pad,
-    int hkv, int d) {
+    int hkv, int d, int* marked) {
     __shared__ bf16_t tile[64][64 + 2];
+    // this pre-pass also clears the count of tiles marked for the repair pass
+    if (marked && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *marked = 0;
     const int t0 = blockIdx.x * 64;
     const int c0 = blockIdx.y * 64;  // column in the flattened [hkv * D] axis
     const int tid = threadIdx.x;
@@ -436,7 +440,7 @@ size_t attn_vt_bytes(const pkv_layer_cfg& cfg, int64_t n_keys) {
 }
 size_t attn_flag_bytes(const pkv_layer_cfg& cfg, int64_t m) {
     const int bm = 256 / (cfg.n_q_heads / cfg.n_kv_heads);
-    return (size_t)ceil_div(m, bm) * cfg.n_kv_heads * sizeof(int);
+    return ((size_t)ceil_div(m, bm) * cfg.n_kv_heads + 1) * sizeof(int);   // + marked count
 }
 
 template <int D, bool kPV>
@@ -505,7 +509,12 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         hipLaunchKernelGGL(transpose_v_kernel,
                            dim3((unsigned)(n_pad / 64), (unsigned)(cfg.n_kv_heads * d / 64)),
                            dim3(256), 0, st, (const bf16_t*)v_cache, vt, (int)n_keys, n_pad,
-                           cfg.n_kv_heads, d);
+                           cfg.n_kv_heads, d,
+                           d == 128 ? reinterpret_cast<int*>((unsigned char*)ws +
+                                                             attn_vt_bytes(cfg, n_keys)) +
+                                          ceil_div(m, 256 / (cfg.n_q_heads / cfg.n_kv_heads)) *
+                                              cfg.n_kv_heads
+                                    : nullptr);
         if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
         AttnParams p = {};
         p.q = (const bf16_t*)q;

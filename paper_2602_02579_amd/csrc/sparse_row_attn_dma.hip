@@ -431,8 +431,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         if (__any(bad) && lane == 0) s_red[wave] = 1 << 30;   // s_red held tile limits so far
         else if (lane == 0) s_red[wave] = 0;
         __syncthreads();
-        if (tid == 0)
-            p.flags[tile * p.hkv + g] = (s_red[0] | s_red[1] | s_red[2] | s_red[3]) != 0;
+        if (tid == 0) {
+            const int marked = (s_red[0] | s_red[1] | s_red[2] | s_red[3]) != 0;
+            p.flags[tile * p.hkv + g] = marked;
+            if (marked) atomicAdd(&p.flags[p.n_tiles * p.hkv], 1);   // count behind the flags
+        }
     }
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {

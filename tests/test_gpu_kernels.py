@@ -192,6 +192,30 @@ def test_query_score_matches_oracle(gpu_device, dtype, nq, n_ctx, hq, hkv, d):
     assert torch.equal(s2, s3)
 
 
+def test_query_score_late_keys_far_above_the_first_tile(gpu_device):
+    """Scores that grow by hundreds of nats after the first 64 keys of a split: the
+    head_dim-128 kernel fixes its softmax reference on the first tile and must raise it
+    (rescaling its sums) when later probabilities leave the safe range."""
+    dtype, nq, n_ctx, hq, hkv, d = "bf16", 40, 3000, 8, 2, 128
+    cfg = lcfg(dtype, hq, hkv, d)
+    q = rnd(40, (nq, hq, d), dtype, 1.0)
+    k = rnd(41, (n_ctx, hkv, d), dtype, 0.05)
+    q[10:, 2, :] = 4.0                       # some columns only
+    k[200::5, 0, :] = 4.0                    # aligned keys: q.k ~ 2048 -> ~180 nats
+    k[1500::11, 0, :] = 6.0                  # and another step up later on
+    q, k = synth.to_storage(q, dtype), synth.to_storage(k, dtype)
+    want = O.query_score(q.astype(np.float64), k.astype(np.float64))
+    score = torch.empty(n_ctx, dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, cfg, n_ctx, nq), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    api.pkv_query_score(cfg, dev(q, dtype, gpu_device), dev(k, dtype, gpu_device), score,
+                        accumulate=False, ws=ws)
+    got = host(score)
+    assert np.isfinite(got).all()
+    assert rel_err(got, want) <= 1e-4
+    assert abs(got.sum() - 1.0) < 1e-4
+
+
 def test_query_score_custom_scale(gpu_device):
     cfg = lcfg("f32", 2, 2, 32)
     q, k = rnd(12, (4, 2, 32), "f32"), rnd(13, (200, 2, 32), "f32")
