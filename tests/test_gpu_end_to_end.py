@@ -1,4 +1,4 @@
-"""GPU parity of the whole hot path against the CPU oracle on BASELINE-shaped
+"""GPU parity of the whole hot path against the CPU oracle on the benchmark-shaped
 synthetic workloads (planted, with an empty guard band at the top-k boundary).
 
 Bar: the selected index set is bit-exact; rows that are not selected stay
