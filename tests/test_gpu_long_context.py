@@ -1,0 +1,87 @@
+"""GPU parity at the largest context of the workload list (256 chunks x 512 tokens,
+N = 131072, Llama-3-8B layer geometry, bf16): the calls whose loops and offsets grow
+with the context, each against the CPU oracle.  The oracle is evaluated in full for
+the restore, the score and the selection, and on a seeded sample of rows for the
+attention (a row costs 32 x 131k x 128 fp64 multiply-adds)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pkv_oracle as O
+from paper_2602_02579_amd import api, synth
+
+pytestmark = pytest.mark.gpu
+
+N_CTX, N_QUERY, HQ, HKV, D = 131072, 256, 32, 8, 128
+
+
+def rnd(seed, shape, scale=1.0):
+    g = np.random.default_rng(seed)
+    x = g.standard_normal(shape, dtype=np.float32) * np.float32(scale)
+    return synth.to_storage(x, "bf16")
+
+
+def host(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def bf16_dev(x, device):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(torch.bfloat16).to(device)
+
+
+def test_attention_over_a_131k_cache_on_sampled_rows(gpu_device):
+    cfg = api.LayerCfg(HQ, HKV, D, 4096, 5e5, "bf16")
+    n_keys = N_CTX + N_QUERY
+    g = np.random.default_rng(501)
+    kc, vc = rnd(502, (n_keys, HKV, D)), rnd(503, (n_keys, HKV, D))
+    # 4096 recomputed rows: a sorted sample of the context plus all the query rows
+    pos = np.concatenate([np.sort(g.choice(N_CTX, 4096 - N_QUERY, replace=False)),
+                          np.arange(N_CTX, n_keys)]).astype(np.int32)
+    m = pos.shape[0]
+    q = rnd(504, (m, HQ, D), 1.2)
+    out = torch.empty((m, HQ, D), dtype=torch.bfloat16, device=gpu_device)
+    lse = torch.empty((m, HQ), dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, m),
+                     dtype=torch.uint8, device=gpu_device)
+    api.pkv_sparse_row_attn(cfg, bf16_dev(q, gpu_device), bf16_dev(kc, gpu_device),
+                            bf16_dev(vc, gpu_device), torch.from_numpy(pos).to(gpu_device),
+                            out, lse, ws=ws)
+    torch.cuda.synchronize()
+    sample = np.unique(np.concatenate([[0, 1, m - 1, m - N_QUERY, m - N_QUERY - 1],
+                                       g.choice(m, 7, replace=False)]))
+    want, want_lse = O.sparse_row_attn(q[sample].astype(np.float64), kc.astype(np.float64),
+                                       vc.astype(np.float64), pos[sample], dtype="bf16")
+    got, got_lse = host(out)[sample], host(lse)[sample]
+    assert np.isfinite(host(out)).all()
+    assert np.abs(got - want).max() / np.abs(want).max() <= 2e-2
+    assert np.abs(got_lse - want_lse).max() <= 4e-3
+
+
+def test_restore_score_and_selection_at_131k(gpu_device):
+    cfg = api.LayerCfg(HQ, HKV, D, 4096, 5e5, "bf16")
+    nq = 16   # 512 (query token, head) columns keep the oracle's [columns, N] matrix small
+    k_nope = rnd(511, (N_CTX, HKV, D))
+    qs = rnd(512, (nq, HQ, D), 1.3)
+    k_dev = bf16_dev(k_nope, gpu_device)
+    k_rope = torch.empty_like(k_dev)
+    api.pkv_rope_restore(cfg, k_dev, k_rope)
+    want_k = O.rope_restore(k_nope.astype(np.float64), np.arange(N_CTX), 5e5, "bf16")
+    got_k = host(k_rope)
+    assert np.abs(got_k - want_k).max() / np.abs(want_k).max() <= 2e-2
+    # the score is taken on the ORACLE's restored keys on both sides, so that it is
+    # compared on identical inputs
+    k_in = bf16_dev(want_k, gpu_device)
+    score = torch.empty(N_CTX, dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, cfg, N_CTX, nq),
+                     dtype=torch.uint8, device=gpu_device)
+    api.pkv_query_score(cfg, bf16_dev(qs, gpu_device), k_in, score, accumulate=False, ws=ws)
+    want_s = O.query_score(qs.astype(np.float64), want_k)
+    got_s = host(score)
+    assert abs(got_s.sum() - 1.0) < 1e-4
+    assert np.abs(got_s - want_s).max() / want_s.max() <= 1e-4
+    # selection from the GPU's own scores: bit-exact against a host sort of those scores
+    k_sel = synth.select_count(0.2, N_CTX)
+    idx = torch.empty(k_sel, dtype=torch.int32, device=gpu_device)
+    api.pkv_topk_select(score, k_sel, idx)
+    assert np.array_equal(idx.cpu().numpy(), O.topk_select(score.cpu().numpy(), k_sel))

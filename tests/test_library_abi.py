@@ -66,3 +66,23 @@ def test_argument_errors_are_reported_without_a_gpu():
                                    4, 10, 0.0, None, 0, None) == 1
     c2 = api.LayerCfg(32, 8, 72, 4096, 5e5, "bf16")._c()
     assert lib.pkv_rope_restore(ctypes.byref(c2), None, None, None, 0, 5, None) == 3
+
+
+def test_a_missing_library_fails_loudly_and_nothing_falls_back():
+    """The binding has no CPU path: with the shared library absent, the first call
+    raises (checked in a fresh interpreter so that this process keeps its library)."""
+    import subprocess
+    import sys
+    code = (
+        "import os, sys\n"
+        "os.environ['PKV_LIBRARY'] = '/nonexistent/libpkv.so'\n"
+        "import torch\n"
+        "from paper_2602_02579_amd import api\n"
+        "try:\n"
+        "    api.pkv_topk_select(torch.zeros(8), 2, torch.zeros(2, dtype=torch.int32))\n"
+        "except RuntimeError as e:\n"
+        "    assert 'missing' in str(e) and 'no CPU fallback' in str(e), str(e)\n"
+        "    sys.exit(0)\n"
+        "sys.exit(1)\n")
+    res = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout + res.stderr
