@@ -217,6 +217,82 @@ pkv_status pkv_sparse_row_attn(const pkv_layer_cfg* cfg,
 size_t pkv_workspace_bytes(int which_call, const pkv_layer_cfg* cfg,
                            int64_t n, int64_t m);
 
+/*
+ * ---- Layer glue for the carried rows -----------------------------------
+ *
+ * Between two runs of the hot path the rows that ProphetKV carries through
+ * the model (Sec. 4.2: the user query, run against the imprecise cache to
+ * obtain its attention to the context; Sec. 4.3 and Appendix E: the selected
+ * and the query rows, through every layer) pass through the rest of a decoder
+ * layer.  The paper evaluates Llama-3.1-8B and Qwen models (Sec. 5.1) and does
+ * not restate their block; the three calls below are the public pre-norm
+ * Llama block, not something the paper defines:
+ *
+ *     x  = rmsnorm(h, w_in)            -> pkv_gather_qkv_proj, ..., attention a
+ *     h' = h + a Wo^T                  (pkv_linear_rows with a residual)
+ *     y  = rmsnorm(h', w_post)
+ *     g  = silu(y Wg^T) * (y Wu^T)     (pkv_swiglu_rows)
+ *     h''= h' + g Wd^T                 (pkv_linear_rows with a residual)
+ *
+ * They take no pkv_layer_cfg: `dtype` is a pkv_dtype and the matrix sizes are
+ * arguments.  Rounding: every tensor these calls write is rounded once to
+ * `dtype`; where a residual is added the product is rounded first and the sum
+ * again, and pkv_swiglu_rows rounds the gate product, its activation, the up
+ * product and the final product separately - the values a framework that
+ * keeps each of these tensors in `dtype` would hold.  Accumulation is fp32.
+ */
+
+/*
+ * y[i, :] = h[row_idx[i], :] / sqrt(mean_j h[row_idx[i], j]^2 + eps) * weight
+ * for i < m; row_idx == NULL means row i.  The mean of squares and the scaling
+ * are fp32.  hidden must be a multiple of 8 and at most 16384.  y must not
+ * overlap h.  m == 0 is a no-op.
+ */
+pkv_status pkv_rmsnorm_rows(int32_t dtype,
+                            const void* h,          /* [>= max row + 1, hidden] */
+                            const int32_t* row_idx, /* [m] or NULL */
+                            const void* weight,     /* [hidden] */
+                            float eps,
+                            void* y,                /* [m, hidden] */
+                            int64_t m, int64_t hidden, void* stream);
+
+/*
+ * y = round(x W^T), then, if residual != NULL, y = round(y + residual).
+ * y may be the same buffer as residual (each element is read before it is
+ * written, by the same thread); it must not overlap x or w.  k_in and n_out
+ * must be multiples of 8.  Scratch: pkv_glue_workspace_bytes(dtype, m, k_in,
+ * n_out); its contents are garbage afterwards.  m == 0 is a no-op.
+ */
+pkv_status pkv_linear_rows(int32_t dtype,
+                           const void* x,        /* [m, k_in] */
+                           const void* w,        /* [n_out, k_in] */
+                           const void* residual, /* [m, n_out] or NULL */
+                           void* y,              /* [m, n_out] */
+                           int64_t m, int64_t k_in, int64_t n_out,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * y = round(round(silu(round(x Wg^T))) * round(x Wu^T)), silu(a) = a / (1 + e^-a).
+ * Same size rules, scratch and aliasing rules as pkv_linear_rows (n_out is
+ * the intermediate size; the scratch of pkv_glue_workspace_bytes covers both
+ * calls for the same m, k_in and n_out).
+ */
+pkv_status pkv_swiglu_rows(int32_t dtype,
+                           const void* x,        /* [m, k_in] */
+                           const void* w_gate,   /* [n_out, k_in] */
+                           const void* w_up,     /* [n_out, k_in] */
+                           void* y,              /* [m, n_out] */
+                           int64_t m, int64_t k_in, int64_t n_out,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Scratch bytes pkv_linear_rows and pkv_swiglu_rows need for these sizes
+ * (the larger of the two).  Pure host function; 0 for invalid arguments or
+ * when none is needed.
+ */
+size_t pkv_glue_workspace_bytes(int32_t dtype, int64_t m, int64_t k_in,
+                                int64_t n_out);
+
 /* Static, never-NULL description of a status code. */
 const char* pkv_status_string(pkv_status status);
 

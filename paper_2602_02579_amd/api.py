@@ -19,6 +19,8 @@ import torch
 __all__ = ["LayerCfg", "PkvError", "load_library", "library_path",
            "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
            "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
+           "pkv_rmsnorm_rows", "pkv_linear_rows", "pkv_swiglu_rows",
+           "pkv_glue_workspace_bytes",
            "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
            "EXPORTED_SYMBOLS"]
 
@@ -29,6 +31,7 @@ CALL_GATHER_QKV_PROJ, CALL_SCATTER_KV, CALL_SPARSE_ROW_ATTN = 4, 5, 6
 EXPORTED_SYMBOLS = [
     "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
     "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
+    "pkv_rmsnorm_rows", "pkv_linear_rows", "pkv_swiglu_rows", "pkv_glue_workspace_bytes",
     "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
 ]
 
@@ -98,8 +101,17 @@ def load_library() -> ctypes.CDLL:
     lib.pkv_scatter_kv.argtypes = [cfgp, vp, vp, i32p, vp, vp, i64, i64, vp]
     lib.pkv_sparse_row_attn.argtypes = [cfgp, vp, vp, vp, i32p, vp, f32p, i64, i64,
                                         ctypes.c_float, vp, ctypes.c_size_t, vp]
+    i32 = ctypes.c_int32
+    lib.pkv_rmsnorm_rows.argtypes = [i32, vp, i32p, vp, ctypes.c_float, vp, i64, i64, vp]
+    lib.pkv_linear_rows.argtypes = [i32, vp, vp, vp, vp, i64, i64, i64, vp,
+                                    ctypes.c_size_t, vp]
+    lib.pkv_swiglu_rows.argtypes = [i32, vp, vp, vp, vp, i64, i64, i64, vp,
+                                    ctypes.c_size_t, vp]
+    lib.pkv_glue_workspace_bytes.argtypes = [i32, i64, i64, i64]
+    lib.pkv_glue_workspace_bytes.restype = ctypes.c_size_t
     for name in ("pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
-                 "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn"):
+                 "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
+                 "pkv_rmsnorm_rows", "pkv_linear_rows", "pkv_swiglu_rows"):
         getattr(lib, name).restype = ctypes.c_int
     lib.pkv_workspace_bytes.argtypes = [ctypes.c_int, cfgp, i64, i64]
     lib.pkv_workspace_bytes.restype = ctypes.c_size_t
@@ -267,3 +279,61 @@ def pkv_sparse_row_attn(cfg: LayerCfg, q: torch.Tensor, k_cache: torch.Tensor,
         _ptr(v_cache, dt, "v_cache"), _ptr(row_pos, torch.int32, "row_pos"),
         _ptr(out, dt, "out"), _ptr(lse_out, torch.float32, "lse_out"), m, n_keys,
         float(softmax_scale), wp, wb, _stream()))
+
+
+# ---- layer glue -------------------------------------------------------------------
+
+def _dtype_code(t: torch.Tensor) -> int:
+    try:
+        return {torch.float32: PKV_F32, torch.bfloat16: PKV_BF16}[t.dtype]
+    except KeyError:
+        raise ValueError(f"dtype {t.dtype} is not supported (fp32 or bf16)") from None
+
+
+def pkv_glue_workspace_bytes(dtype: torch.dtype, m: int, k_in: int, n_out: int) -> int:
+    code = {torch.float32: PKV_F32, torch.bfloat16: PKV_BF16}[dtype]
+    return int(load_library().pkv_glue_workspace_bytes(code, m, k_in, n_out))
+
+
+def pkv_rmsnorm_rows(h: torch.Tensor, row_idx: Optional[torch.Tensor],
+                     weight: torch.Tensor, eps: float, y: torch.Tensor) -> None:
+    m, hidden = y.shape
+    dt = h.dtype
+    if h.dim() != 2 or h.shape[1] != hidden or tuple(weight.shape) != (hidden,):
+        raise ValueError("h must be [rows, hidden], weight [hidden], y [m, hidden]")
+    if row_idx is not None and tuple(row_idx.shape) != (m,):
+        raise ValueError("row_idx must be [m]")
+    if row_idx is None and h.shape[0] < m:
+        raise ValueError("h has fewer than m rows")
+    _check("pkv_rmsnorm_rows", load_library().pkv_rmsnorm_rows(
+        _dtype_code(h), _ptr(h, dt, "h"), _ptr(row_idx, torch.int32, "row_idx"),
+        _ptr(weight, dt, "weight"), float(eps), _ptr(y, dt, "y"), m, hidden, _stream()))
+
+
+def pkv_linear_rows(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor],
+                    y: torch.Tensor, ws: Optional[torch.Tensor] = None) -> None:
+    m, k_in = x.shape
+    n_out = w.shape[0]
+    dt = x.dtype
+    if tuple(w.shape) != (n_out, k_in) or tuple(y.shape) != (m, n_out):
+        raise ValueError("w must be [n_out, k_in] and y [m, n_out]")
+    if residual is not None and tuple(residual.shape) != (m, n_out):
+        raise ValueError("residual must be [m, n_out]")
+    wp, wb = _ws(ws)
+    _check("pkv_linear_rows", load_library().pkv_linear_rows(
+        _dtype_code(x), _ptr(x, dt, "x"), _ptr(w, dt, "w"), _ptr(residual, dt, "residual"),
+        _ptr(y, dt, "y"), m, k_in, n_out, wp, wb, _stream()))
+
+
+def pkv_swiglu_rows(x: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor,
+                    y: torch.Tensor, ws: Optional[torch.Tensor] = None) -> None:
+    m, k_in = x.shape
+    n_out = w_gate.shape[0]
+    dt = x.dtype
+    if tuple(w_gate.shape) != (n_out, k_in) or w_up.shape != w_gate.shape or \
+            tuple(y.shape) != (m, n_out):
+        raise ValueError("w_gate/w_up must be [n_out, k_in] and y [m, n_out]")
+    wp, wb = _ws(ws)
+    _check("pkv_swiglu_rows", load_library().pkv_swiglu_rows(
+        _dtype_code(x), _ptr(x, dt, "x"), _ptr(w_gate, dt, "w_gate"), _ptr(w_up, dt, "w_up"),
+        _ptr(y, dt, "y"), m, k_in, n_out, wp, wb, _stream()))

@@ -62,8 +62,11 @@ __device__ __forceinline__ void wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-__global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int n_tok_tiles,
-                                                              int n_tiles, int per_xcd) {
+__device__ __forceinline__ float silu_f32(float a) { return a / (1.f + __expf(-a)); }
+
+template <int MODE>
+__global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_tiles,
+                                                       int n_tiles, int per_xcd) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -85,8 +88,10 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
     const int tok_tile = first_tok + within % rows_in_group;
     const int ft = within / rows_in_group;
     int mat = 0;
-    if (ft >= p.tile_begin[1]) mat = 1;
-    if (ft >= p.tile_begin[2]) mat = 2;
+    if (MODE == kProjRope) {
+        if (ft >= p.tile_begin[1]) mat = 1;
+        if (ft >= p.tile_begin[2]) mat = 2;
+    }
     const int feat0 = (ft - p.tile_begin[mat]) * T;   // first output feature of the tile
     const bf16_t* w = p.w[mat];
     bf16_t* out = p.out[mat];
@@ -106,7 +111,15 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
         const int gr = min(row0 + r, p.m - 1);
         const int64_t src_row = p.row_idx ? p.row_idx[gr] : gr;
         xptr[j] = p.hidden + src_row * p.hid + k_begin + sw * 8;
-        wptr[j] = w + (int64_t)(feat0 + r) * p.hid + k_begin + sw * 8;
+        if (MODE == kProjGated) {
+            // tile row r: half r / 128 of the tile's 128 outputs, then 64 gate rows and
+            // 64 up rows, so that accumulator blocks (0, 1) and (2, 3) of a wave hold
+            // gate and up of the same outputs
+            const int f = ft * 128 + (r >> 7) * 64 + (r & 63);
+            wptr[j] = p.w[(r >> 6) & 1] + (int64_t)f * p.hid + k_begin + sw * 8;
+        } else {
+            wptr[j] = w + (int64_t)(feat0 + r) * p.hid + k_begin + sw * 8;
+        }
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
     const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(lds0 + wave * 4 * 1024);
@@ -236,9 +249,83 @@ __global__ __launch_bounds__(256) void qkv_proj_dma128_kernel(ProjParams p, int 
         }
         return;
     }
+    unsigned char* epi = smem + wave * (64 * kEpiStride);
+    if (MODE == kProjPlain) {
+        // the wave's 128 tokens x 128 outputs: round the products, stage, then add the
+        // residual (if any) 16 B per lane and round again
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int tbl = 0; tbl < 2; ++tbl) {
+                const int tb = half * 2 + tbl;
+                unsigned char* erow = epi + (tbl * 32 + l32) * kEpiStride;
+#pragma unroll
+                for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        bf16x4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)acc[fb][tb][4 * j + e];
+                        *reinterpret_cast<bf16x4*>(erow + (fb * 32 + 8 * j + 4 * hh) * 2) = v;
+                    }
+            }
+#pragma unroll
+            for (int it = 0; it < 16; ++it) {
+                const int idx = it * 64 + lane;
+                const int tok = idx >> 4, ch = idx & 15;
+                const int row = row0 + wt * 128 + half * 64 + tok;
+                bf16x8 v = *reinterpret_cast<const bf16x8*>(epi + tok * kEpiStride + ch * 16);
+                if (row < p.m) {
+                    const int64_t o = (int64_t)row * p.n_out + feat0 + wf * 128 + ch * 8;
+                    if (p.residual) {
+                        const bf16x8 r = *reinterpret_cast<const bf16x8*>(p.residual + o);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = (bf16_t)((float)v[e] + (float)r[e]);
+                    }
+                    *reinterpret_cast<bf16x8*>(out + o) = v;
+                }
+            }
+        }
+        return;
+    }
+    if (MODE == kProjGated) {
+        // the wave's 128 tokens x 64 outputs: gate in blocks 0, 1 and up in blocks 2, 3
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int tbl = 0; tbl < 2; ++tbl) {
+                const int tb = half * 2 + tbl;
+                unsigned char* erow = epi + (tbl * 32 + l32) * kEpiStride;
+#pragma unroll
+                for (int fbp = 0; fbp < 2; ++fbp)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        bf16x4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float a = (float)(bf16_t)acc[fbp][tb][4 * j + e];
+                            const float b = (float)(bf16_t)acc[fbp + 2][tb][4 * j + e];
+                            const float s = (float)(bf16_t)silu_f32(a);
+                            v[e] = (bf16_t)(s * b);
+                        }
+                        *reinterpret_cast<bf16x4*>(erow + (fbp * 32 + 8 * j + 4 * hh) * 2) = v;
+                    }
+            }
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int idx = it * 64 + lane;
+                const int tok = idx >> 3, ch = idx & 7;
+                const int row = row0 + wt * 128 + half * 64 + tok;
+                const uint4 v = *reinterpret_cast<const uint4*>(epi + tok * kEpiStride + ch * 16);
+                if (row < p.m)
+                    *reinterpret_cast<uint4*>(out + (int64_t)row * p.n_out + ft * 128 + wf * 64 +
+                                              ch * 8) = v;
+            }
+        }
+        return;
+    }
     const int head = feat0 / D + wf;
     const bool rotate = mat != 2;
-    unsigned char* epi = smem + wave * (64 * kEpiStride);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -329,6 +416,43 @@ __global__ __launch_bounds__(256) void proj_splitk_finish_kernel(ProjParams p) {
     o[D / 2] = (bf16_t)b;
 }
 
+// the same for the plain and the gated linear layers: one thread per (row, 4 outputs)
+template <int MODE>
+__global__ __launch_bounds__(256) void linear_splitk_finish_kernel(ProjParams p) {
+    const int f_total = T * p.tile_begin[3];
+    const int quads = p.n_out / 4;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)p.m * quads) return;
+    const int row = (int)(idx / quads);
+    const int f = (int)(idx % quads) * 4;
+    // column of output f in the tile order of the partials
+    const int col = MODE == kProjGated ? (f >> 7) * T + ((f >> 6) & 1) * 128 + (f & 63) : f;
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < p.n_ksplit; ++s) {
+        const float* src = p.partial + ((int64_t)s * p.m + row) * f_total + col;
+        a += *reinterpret_cast<const f32x4*>(src);
+        if (MODE == kProjGated) b += *reinterpret_cast<const f32x4*>(src + 64);
+    }
+    const int64_t o = (int64_t)row * p.n_out + f;
+    bf16x4 v;
+    if (MODE == kProjGated) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float ar = (float)(bf16_t)a[e], br = (float)(bf16_t)b[e];
+            v[e] = (bf16_t)((float)(bf16_t)silu_f32(ar) * br);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)a[e];
+        if (p.residual) {
+            const bf16x4 r = *reinterpret_cast<const bf16x4*>(p.residual + o);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (bf16_t)((float)v[e] + (float)r[e]);
+        }
+    }
+    *reinterpret_cast<bf16x4*>(p.out[0] + o) = v;
+}
+
 // splits of the contraction for a launch of n_tiles tiles over n_k stages: the largest
 // power of two that keeps the launch within ~256 workgroups and a split >= NS stages
 int plan_ksplit(int64_t n_tiles, int n_k) {
@@ -354,10 +478,13 @@ bool proj_dma128_supported(const pkv_layer_cfg& cfg, int64_t m) {
            m > 0 && m < (1 << 30);
 }
 
-pkv_status launch_proj_dma128(const ProjParams& p, hipStream_t st) {
+namespace {
+
+template <int MODE>
+pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(qkv_proj_dma128_kernel),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(proj_dma_kernel<MODE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
@@ -371,14 +498,61 @@ pkv_status launch_proj_dma128(const ProjParams& p, hipStream_t st) {
     q.n_ksplit = plan_ksplit(n_tiles, p.hid / BK);
     if (q.n_ksplit > 1 && q.partial == nullptr) return PKV_ERR_WORKSPACE;
     const int per_xcd = (int)ceil_div(n_tiles * q.n_ksplit, 8);
-    hipLaunchKernelGGL(qkv_proj_dma128_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256),
+    hipLaunchKernelGGL(proj_dma_kernel<MODE>, dim3((unsigned)(per_xcd * 8)), dim3(256),
                        kLdsBytes, st, q, n_tok_tiles, (int)n_tiles, per_xcd);
     if (q.n_ksplit > 1) {
-        const int64_t total = (int64_t)p.m * (T * p.tile_begin[3] / 2);
-        hipLaunchKernelGGL(proj_splitk_finish_kernel, dim3((unsigned)ceil_div(total, 256)),
-                           dim3(256), 0, st, q);
+        if (MODE == kProjRope) {
+            const int64_t total = (int64_t)p.m * (T * p.tile_begin[3] / 2);
+            hipLaunchKernelGGL(proj_splitk_finish_kernel, dim3((unsigned)ceil_div(total, 256)),
+                               dim3(256), 0, st, q);
+        } else {
+            const int64_t total = (int64_t)p.m * (p.n_out / 4);
+            hipLaunchKernelGGL(linear_splitk_finish_kernel<MODE>,
+                               dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, st, q);
+        }
     }
     return launch_status();
+}
+
+}  // namespace
+
+pkv_status launch_proj_dma128(const ProjParams& p, hipStream_t st) {
+    return launch_tiles<kProjRope>(p, st);
+}
+
+bool linear_dma_supported(int mode, int64_t m, int64_t k_in, int64_t n_out) {
+    const int64_t per_tile = mode == kProjGated ? T / 2 : T;
+    return m > 0 && m < (1 << 30) && k_in % BK == 0 && k_in / BK >= NS && k_in < (1 << 30) &&
+           n_out > 0 && n_out % per_tile == 0 && n_out < (1 << 30);
+}
+
+size_t linear_dma_partial_bytes(int64_t m) {
+    // as for the Q/K/V launch: splits x features <= 256 tiles' worth
+    const int64_t n_tok_tiles = ceil_div(m, T);
+    if (m <= 0 || n_tok_tiles > 128) return 0;
+    return (size_t)m * (size_t)(T * 256 / n_tok_tiles) * sizeof(float);
+}
+
+pkv_status launch_linear_dma(int mode, const bf16_t* x, const bf16_t* w0, const bf16_t* w1,
+                             const bf16_t* residual, bf16_t* y, int64_t m, int64_t k_in,
+                             int64_t n_out, float* partial, hipStream_t st) {
+    ProjParams p = {};
+    p.hidden = x;
+    p.row_idx = nullptr;
+    p.w[0] = w0;
+    p.w[1] = w1;
+    p.out[0] = y;
+    p.cs = nullptr;
+    p.m = (int)m;
+    p.hid = (int)k_in;
+    const int nft = (int)(n_out / (mode == kProjGated ? T / 2 : T));
+    p.tile_begin[0] = 0;
+    p.tile_begin[1] = p.tile_begin[2] = p.tile_begin[3] = nft;
+    p.partial = partial;
+    p.n_ksplit = 1;
+    p.residual = residual;
+    p.n_out = (int)n_out;
+    return mode == kProjGated ? launch_tiles<kProjGated>(p, st) : launch_tiles<kProjPlain>(p, st);
 }
 
 }  // namespace pkv

@@ -122,6 +122,57 @@ pkv_status pkv_sparse_row_attn(const pkv_layer_cfg* cfg, const void* q,
                                   ws, (hipStream_t)stream);
 }
 
+pkv_status pkv_rmsnorm_rows(int32_t dtype, const void* h, const int32_t* row_idx,
+                            const void* weight, float eps, void* y, int64_t m,
+                            int64_t hidden, void* stream) {
+    if (dtype != PKV_F32 && dtype != PKV_BF16) return PKV_ERR_UNSUPPORTED;
+    if (m < 0 || m > kMaxTokens || hidden <= 0) return PKV_ERR_SHAPE;
+    if (hidden % 8 || hidden > 16384) return PKV_ERR_UNSUPPORTED;
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return PKV_ERR_SHAPE;
+    if (m == 0) return PKV_OK;
+    if (!h || !weight || !y) return PKV_ERR_NULL;
+    return launch_rmsnorm_rows(dtype, h, row_idx, weight, eps, y, m, hidden,
+                               (hipStream_t)stream);
+}
+
+static pkv_status linear_checked(int32_t dtype, bool gated, const void* x, const void* w0,
+                                 const void* w1, const void* residual, void* y, int64_t m,
+                                 int64_t k_in, int64_t n_out, void* ws, size_t ws_bytes,
+                                 void* stream) {
+    if (dtype != PKV_F32 && dtype != PKV_BF16) return PKV_ERR_UNSUPPORTED;
+    if (m < 0 || m > kMaxTokens || k_in <= 0 || n_out <= 0 || k_in > kMaxTokens ||
+        n_out > kMaxTokens)
+        return PKV_ERR_SHAPE;
+    if (k_in % 8 || n_out % 8) return PKV_ERR_UNSUPPORTED;
+    if (m == 0) return PKV_OK;
+    if (!x || !w0 || !y || (gated && !w1)) return PKV_ERR_NULL;
+    const size_t need = align256(glue_ws_bytes(dtype, m, k_in, n_out));
+    if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
+    return launch_linear_rows(dtype, gated, x, w0, w1, residual, y, m, k_in, n_out, ws,
+                              (hipStream_t)stream);
+}
+
+pkv_status pkv_linear_rows(int32_t dtype, const void* x, const void* w, const void* residual,
+                           void* y, int64_t m, int64_t k_in, int64_t n_out, void* ws,
+                           size_t ws_bytes, void* stream) {
+    return linear_checked(dtype, false, x, w, nullptr, residual, y, m, k_in, n_out, ws,
+                          ws_bytes, stream);
+}
+
+pkv_status pkv_swiglu_rows(int32_t dtype, const void* x, const void* w_gate, const void* w_up,
+                           void* y, int64_t m, int64_t k_in, int64_t n_out, void* ws,
+                           size_t ws_bytes, void* stream) {
+    return linear_checked(dtype, true, x, w_gate, w_up, nullptr, y, m, k_in, n_out, ws,
+                          ws_bytes, stream);
+}
+
+size_t pkv_glue_workspace_bytes(int32_t dtype, int64_t m, int64_t k_in, int64_t n_out) {
+    if ((dtype != PKV_F32 && dtype != PKV_BF16) || m <= 0 || k_in <= 0 || n_out <= 0 ||
+        m > kMaxTokens || k_in > kMaxTokens || n_out > kMaxTokens)
+        return 0;
+    return align256(glue_ws_bytes(dtype, m, k_in, n_out));
+}
+
 size_t pkv_workspace_bytes(int which_call, const pkv_layer_cfg* cfg, int64_t n,
                            int64_t m) {
     if (check_cfg(cfg) != PKV_OK || n < 0 || m < 0) return 0;
