@@ -257,6 +257,18 @@ pkv_status pkv_rmsnorm_rows(int32_t dtype,
                             int64_t m, int64_t hidden, void* stream);
 
 /*
+ * dst[i, :] = src[row_idx[i], :] for i < m: the hidden states of the carried
+ * rows at the first layer (Appendix E: the hidden states are pruned to the
+ * selected tokens).  `width` elements per row, a multiple of 8; src, dst
+ * 16-byte aligned and not overlapping.  m == 0 is a no-op.
+ */
+pkv_status pkv_gather_rows(int32_t dtype,
+                           const void* src,        /* [>= max row + 1, width] */
+                           const int32_t* row_idx, /* [m] */
+                           void* dst,              /* [m, width] */
+                           int64_t m, int64_t width, void* stream);
+
+/*
  * y = round(x W^T), then, if residual != NULL, y = round(y + residual).
  * y may be the same buffer as residual (each element is read before it is
  * written, by the same thread); it must not overlap x or w.  k_in and n_out

@@ -19,7 +19,7 @@ import torch
 __all__ = ["LayerCfg", "PkvError", "load_library", "library_path",
            "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
            "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
-           "pkv_rmsnorm_rows", "pkv_linear_rows", "pkv_swiglu_rows",
+           "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
            "pkv_glue_workspace_bytes",
            "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
            "EXPORTED_SYMBOLS"]
@@ -31,7 +31,8 @@ CALL_GATHER_QKV_PROJ, CALL_SCATTER_KV, CALL_SPARSE_ROW_ATTN = 4, 5, 6
 EXPORTED_SYMBOLS = [
     "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
     "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
-    "pkv_rmsnorm_rows", "pkv_linear_rows", "pkv_swiglu_rows", "pkv_glue_workspace_bytes",
+    "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
+    "pkv_glue_workspace_bytes",
     "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
 ]
 
@@ -103,6 +104,7 @@ def load_library() -> ctypes.CDLL:
                                         ctypes.c_float, vp, ctypes.c_size_t, vp]
     i32 = ctypes.c_int32
     lib.pkv_rmsnorm_rows.argtypes = [i32, vp, i32p, vp, ctypes.c_float, vp, i64, i64, vp]
+    lib.pkv_gather_rows.argtypes = [i32, vp, i32p, vp, i64, i64, vp]
     lib.pkv_linear_rows.argtypes = [i32, vp, vp, vp, vp, i64, i64, i64, vp,
                                     ctypes.c_size_t, vp]
     lib.pkv_swiglu_rows.argtypes = [i32, vp, vp, vp, vp, i64, i64, i64, vp,
@@ -111,7 +113,8 @@ def load_library() -> ctypes.CDLL:
     lib.pkv_glue_workspace_bytes.restype = ctypes.c_size_t
     for name in ("pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
                  "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
-                 "pkv_rmsnorm_rows", "pkv_linear_rows", "pkv_swiglu_rows"):
+                 "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows",
+                 "pkv_swiglu_rows"):
         getattr(lib, name).restype = ctypes.c_int
     lib.pkv_workspace_bytes.argtypes = [ctypes.c_int, cfgp, i64, i64]
     lib.pkv_workspace_bytes.restype = ctypes.c_size_t
@@ -308,6 +311,15 @@ def pkv_rmsnorm_rows(h: torch.Tensor, row_idx: Optional[torch.Tensor],
     _check("pkv_rmsnorm_rows", load_library().pkv_rmsnorm_rows(
         _dtype_code(h), _ptr(h, dt, "h"), _ptr(row_idx, torch.int32, "row_idx"),
         _ptr(weight, dt, "weight"), float(eps), _ptr(y, dt, "y"), m, hidden, _stream()))
+
+
+def pkv_gather_rows(src: torch.Tensor, row_idx: torch.Tensor, dst: torch.Tensor) -> None:
+    m, width = dst.shape
+    if src.dim() != 2 or src.shape[1] != width or tuple(row_idx.shape) != (m,):
+        raise ValueError("src must be [rows, width], row_idx [m], dst [m, width]")
+    _check("pkv_gather_rows", load_library().pkv_gather_rows(
+        _dtype_code(src), _ptr(src, src.dtype, "src"), _ptr(row_idx, torch.int32, "row_idx"),
+        _ptr(dst, src.dtype, "dst"), m, width, _stream()))
 
 
 def pkv_linear_rows(x: torch.Tensor, w: torch.Tensor, residual: Optional[torch.Tensor],

@@ -92,6 +92,18 @@ __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(const T* __restrict__
     }
 }
 
+// ---- row gather: 16 bytes per lane ------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ src,
+                                                          const int32_t* __restrict__ row_idx,
+                                                          uint4* __restrict__ dst, int64_t total,
+                                                          int chunks) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int64_t row = i / chunks;
+    const int c = (int)(i - row * chunks);
+    dst[i] = src[(int64_t)row_idx[row] * chunks + c];
+}
+
 // ---- simple linear layers: one wave per output element ----------------------------------
 template <typename T>
 __device__ __forceinline__ float wave_dot(const T* __restrict__ a, const T* __restrict__ b,
@@ -172,6 +184,18 @@ pkv_status launch_rmsnorm_rows(int dtype, const void* h, const int32_t* row_idx,
     return dtype == PKV_BF16
                ? rmsnorm_typed<bf16_t>(h, row_idx, weight, eps, y, m, hidden, st)
                : rmsnorm_typed<float>(h, row_idx, weight, eps, y, m, hidden, st);
+}
+
+pkv_status launch_gather_rows(int dtype, const void* src, const int32_t* row_idx, void* dst,
+                              int64_t m, int64_t width, hipStream_t st) {
+    if (!aligned16(src) || !aligned16(dst)) return PKV_ERR_UNSUPPORTED;
+    const int chunks = (int)(width * (dtype == PKV_BF16 ? 2 : 4) / 16);
+    const int64_t total = m * chunks;
+    const int64_t blocks = ceil_div(total, 256);
+    if (blocks > 0x7fffffff) return PKV_ERR_SHAPE;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       (const uint4*)src, row_idx, (uint4*)dst, total, chunks);
+    return launch_status();
 }
 
 size_t glue_ws_bytes(int dtype, int64_t m, int64_t k_in, int64_t n_out) {

@@ -135,6 +135,16 @@ pkv_status pkv_rmsnorm_rows(int32_t dtype, const void* h, const int32_t* row_idx
                                (hipStream_t)stream);
 }
 
+pkv_status pkv_gather_rows(int32_t dtype, const void* src, const int32_t* row_idx, void* dst,
+                           int64_t m, int64_t width, void* stream) {
+    if (dtype != PKV_F32 && dtype != PKV_BF16) return PKV_ERR_UNSUPPORTED;
+    if (m < 0 || m > kMaxTokens || width <= 0 || width > kMaxTokens) return PKV_ERR_SHAPE;
+    if (width % 8) return PKV_ERR_UNSUPPORTED;
+    if (m == 0) return PKV_OK;
+    if (!src || !row_idx || !dst) return PKV_ERR_NULL;
+    return launch_gather_rows(dtype, src, row_idx, dst, m, width, (hipStream_t)stream);
+}
+
 static pkv_status linear_checked(int32_t dtype, bool gated, const void* x, const void* w0,
                                  const void* w1, const void* residual, void* y, int64_t m,
                                  int64_t k_in, int64_t n_out, void* ws, size_t ws_bytes,

@@ -108,6 +108,8 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
 pkv_status launch_rmsnorm_rows(int dtype, const void* h, const int32_t* row_idx,
                                const void* weight, float eps, void* y, int64_t m,
                                int64_t hidden, hipStream_t st);
+pkv_status launch_gather_rows(int dtype, const void* src, const int32_t* row_idx, void* dst,
+                              int64_t m, int64_t width, hipStream_t st);
 size_t glue_ws_bytes(int dtype, int64_t m, int64_t k_in, int64_t n_out);
 pkv_status launch_linear_rows(int dtype, bool gated, const void* x, const void* w0,
                               const void* w1, const void* residual, void* y, int64_t m,

@@ -30,7 +30,7 @@ import numpy as np
 import torch
 
 __all__ = ["Config", "CONFIGS", "make_layer", "plant", "nudge_keys",
-           "to_storage", "select_count"]
+           "to_storage", "select_count", "make_embed", "make_block_weights"]
 
 
 @dataclass(frozen=True)
@@ -226,3 +226,36 @@ def nudge_keys(cfg: Config, layer: Dict[str, np.ndarray], idx: np.ndarray,
     kr = kr + np.asarray(coeff, np.float64)[:, None, None] * u[None]
     back = np.asarray(rotate(kr, -pos), dtype=np.float64)
     layer["k_nope"][pos] = to_storage(back.astype(np.float32), cfg.dtype)
+
+
+def make_embed(cfg: Config) -> np.ndarray:
+    """Layer-0 hidden state of every prompt token, ``[N + Qn, hid]`` ~ N(0, 1): stands
+    for the embedding lookup of a model whose hidden states are carried through the
+    layers (the rows of the user query share a common component, as in ``make_layer``)."""
+    g = _rng(cfg, 0, 11)
+    e = g.standard_normal((cfg.n_tokens, cfg.hidden), dtype=np.float32)
+    common = g.standard_normal(cfg.hidden, dtype=np.float32)
+    e[cfg.n_ctx:] = np.float32(0.7) * common + np.float32(0.7) * e[cfg.n_ctx:]
+    return to_storage(e, cfg.dtype)
+
+
+def make_block_weights(cfg: Config, layer: int, inter: int) -> Dict[str, np.ndarray]:
+    """Weights of one pre-norm decoder block with a gated MLP of width ``inter``:
+    norm gains ``w_in, w_post [hid]`` ~ 1 + 0.1 N(0,1); ``wq [Hq*D, hid]``,
+    ``wk, wv [Hkv*D, hid]``, ``wo [hid, Hq*D]``, ``w_gate, w_up [inter, hid]``,
+    ``w_down [hid, inter]`` ~ N(0, 1/fan_in) (outputs of unit scale for unit-scale
+    inputs, so that hidden states neither vanish nor blow up over a few layers)."""
+    hq, hkv, d, hid = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.hidden
+    g = _rng(cfg, layer, 12)
+    f32 = np.float32
+
+    def mat(rows, cols, gain=1.0):
+        return f32(gain / np.sqrt(cols)) * g.standard_normal((rows, cols), dtype=f32)
+
+    out = dict(
+        w_in=f32(1.0) + f32(0.1) * g.standard_normal(hid, dtype=f32),
+        w_post=f32(1.0) + f32(0.1) * g.standard_normal(hid, dtype=f32),
+        wq=mat(hq * d, hid, 1.5), wk=mat(hkv * d, hid, 1.5), wv=mat(hkv * d, hid),
+        wo=mat(hid, hq * d), w_gate=mat(inter, hid, 1.5), w_up=mat(inter, hid),
+        w_down=mat(hid, inter))
+    return {k: to_storage(v, cfg.dtype) for k, v in out.items()}

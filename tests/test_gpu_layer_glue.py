@@ -73,6 +73,16 @@ def test_rmsnorm_rows_matches_oracle(gpu_device, dtype, n_rows, m, hidden, gathe
         check_bf16_neighbours(got, want)
 
 
+@pytest.mark.parametrize("dtype,n_rows,m,width", [("bf16", 500, 333, 4096), ("f32", 40, 64, 8),
+                                                   ("bf16", 3, 1000, 136)])
+def test_gather_rows_is_a_bit_exact_copy(gpu_device, dtype, n_rows, m, width):
+    src = rnd(51, (n_rows, width), dtype)
+    idx = np.random.default_rng(52).integers(0, n_rows, size=m).astype(np.int32)
+    dst = torch.empty((m, width), dtype=TDT[dtype], device=gpu_device)
+    api.pkv_gather_rows(dev(src, dtype, gpu_device), torch.from_numpy(idx).to(gpu_device), dst)
+    assert np.array_equal(host(dst), src[idx].astype(np.float64))
+
+
 LINEAR_CASES = [
     # dtype, m, k_in, n_out: tile path unsplit, split (few rows), ragged rows; simple path
     ("bf16", 300, 512, 512), ("bf16", 128, 2048, 256), ("bf16", 1, 4096, 256),

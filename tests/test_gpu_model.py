@@ -1,0 +1,118 @@
+"""GPU parity of both stages with carried hidden states (Stage I on the query rows,
+Stage II on the selected and the query rows, through every layer's attention and
+MLP) against the CPU model oracle, on small seeded models.
+
+Bar: fp32 1e-4, bf16 2e-2 (max|a - b| / max|b|) for scores, caches and hidden
+states.  The selection is compared where it is decided by more than the rounding of
+the scores (tokens outside a guard band around the threshold must agree); Stage II is
+then run on the oracle's selection so that every later tensor is compared like for
+like.  Reused cache rows must be bit-identical to the assembled cache."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pkv_model_oracle as MO
+from paper_2602_02579_amd import model, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+EPS = 1e-5
+
+
+def host(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def rel_err(got, want):
+    return float(np.abs(got - want).max() / max(np.abs(want).max(), 1e-30))
+
+
+def build(cfg, inter):
+    layers = []
+    for li in range(cfg.n_layers):
+        raw = synth.make_layer(cfg, li)
+        layer = dict(k_nope=raw["k_nope"], v=raw["v"])
+        layer.update(synth.make_block_weights(cfg, li, inter))
+        layers.append(layer)
+    return synth.make_embed(cfg), layers
+
+
+CASES = {
+    "f32-small": (synth.Config("model-f32", "f32", 4, 32, 8, 4, 2, 32, 64, 10000.0,
+                               seed=21, n_layers=3, n_score_layers=2), 160),
+    "bf16-tiles": (synth.Config("model-bf16", "bf16", 2, 256, 16, 4, 2, 128, 256, 500000.0,
+                                seed=22, n_layers=3, n_score_layers=2), 512),
+    "bf16-odd": (synth.Config("model-bf16-odd", "bf16", 3, 100, 5, 6, 2, 64, 136, 500000.0,
+                              seed=23, n_layers=2, n_score_layers=1), 200),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_model_matches_oracle(gpu_device, name):
+    cfg, inter = CASES[name]
+    tol = TOL[cfg.dtype]
+    embed, layers = build(cfg, inter)
+    n, qn = cfg.n_ctx, cfg.n_query
+    k = synth.select_count(cfg.ratio, n)
+    geo = dict(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+               theta=cfg.theta)
+    sel, score, want = MO.prophetkv_model(
+        embed, [{a: b.astype(np.float64) for a, b in l.items()} for l in layers], qn, k,
+        cfg.n_score_layers, eps=EPS, dtype=cfg.dtype, **geo)
+
+    dev_layers = [model.upload_block(cfg, l, gpu_device) for l in layers]
+    dev_embed = torch.from_numpy(embed).to(dev_layers[0]["wq"].dtype).to(gpu_device)
+    cr = model.CarriedRows(cfg, inter, EPS, gpu_device)
+    assert cr.k == k
+
+    # ---- Stage I: score, query hidden states after the scoring layers, selection ----
+    cr.stage1(dev_embed, dev_layers)
+    torch.cuda.synchronize()
+    got_score = host(cr.score)
+    assert rel_err(got_score, score) <= (2e-2 if cfg.dtype == "bf16" else 1e-4)
+    assert abs(got_score.sum() - cfg.n_score_layers) < 1e-3
+    assert rel_err(host(cr.h[:qn]), want["stage1_h"][-1]) <= tol
+    got_sel = cr.rows[:k].cpu().numpy()
+    assert np.array_equal(got_sel, np.sort(got_sel)) and len(np.unique(got_sel)) == k
+    srt = np.sort(score)[::-1]
+    tau = 0.5 * (srt[k - 1] + srt[k])
+    band = (5e-2 if cfg.dtype == "bf16" else 1e-3) * tau
+    clear_in = np.nonzero(score > tau + band)[0]
+    clear_out = np.nonzero(score < tau - band)[0]
+    assert np.isin(clear_in, got_sel).all()
+    assert not np.isin(clear_out, got_sel).any()
+
+    # ---- Stage II on the oracle's selection -------------------------------------------
+    cr.rows[:k] = torch.from_numpy(sel.astype(np.int32)).to(gpu_device)
+    h_final = cr.stage2(dev_embed, dev_layers)
+    torch.cuda.synchronize()
+    rows = want["rows"]
+    rest = np.setdiff1d(np.arange(n), sel)
+    for li, L in enumerate(dev_layers):
+        kc, vc = host(L["k_cache"]), host(L["v_cache"])
+        assert rel_err(kc[rows], want["k_cache"][li][rows]) <= tol
+        assert rel_err(vc[rows], want["v_cache"][li][rows]) <= tol
+        assert np.array_equal(vc[rest], want["v_cache"][li][rest])
+        assert rel_err(kc[rest], want["k_cache"][li][rest]) <= tol
+    assert rel_err(host(cr.attn[:cr.m]), want["attn"][-1]) <= tol
+    assert rel_err(host(h_final), want["h_final"]) <= tol
+
+
+def test_model_whole_run_is_deterministic_and_selects_like_stage1(gpu_device):
+    """run() = stage1 + stage2 on the device's own selection; twice the same bits."""
+    cfg, inter = CASES["bf16-tiles"]
+    embed, layers = build(cfg, inter)
+    outs = []
+    for _ in range(2):
+        dev_layers = [model.upload_block(cfg, l, gpu_device) for l in layers]
+        dev_embed = torch.from_numpy(embed).to(torch.bfloat16).to(gpu_device)
+        cr = model.CarriedRows(cfg, inter, EPS, gpu_device)
+        h = cr.run(dev_embed, dev_layers)
+        torch.cuda.synchronize()
+        outs.append((h.clone(), cr.rows.clone(), dev_layers[-1]["k_cache"].clone()))
+    assert torch.equal(outs[0][1], outs[1][1])
+    assert torch.equal(outs[0][0], outs[1][0])
+    assert torch.equal(outs[0][2], outs[1][2])
+    assert torch.isfinite(outs[0][0].float()).all()
