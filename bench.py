@@ -6,8 +6,13 @@ r = 0.2): restore RoPE, project the query rows, score, select, project the
 selected + query rows, scatter, attend.  Inputs are resident in HBM before the
 timed region.  Prints ONE JSON line.
 
+After the timed steps (and outside `value`) it also times the same configuration as
+a small stacked model with the hidden states carried through the layers - Stage I on
+the query rows, Stage II on the selected + query rows, each layer with its output
+projection and gated MLP (Llama-3-8B widths) - and reports it as `carried_model`.
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
-                    [--no-cpu-baseline]
+                    [--no-cpu-baseline] [--model-layers L]
 """
 
 from __future__ import annotations
@@ -25,7 +30,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-from paper_2602_02579_amd import api, pipeline, synth  # noqa: E402
+from paper_2602_02579_amd import api, model, pipeline, synth  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # HBM bytes per pkv_sparse_row_attn launch (V^T pre-pass + main kernel), from the
@@ -178,6 +183,81 @@ def time_calls(fn, reps, batch=10):
     return float(np.median(ts))
 
 
+def carried_model(cfg, device, n_layers, inter=14336, eps=1e-5, steps=3):
+    """One pass = Stage I (query rows, 2 scoring layers) + Stage II (selected + query
+    rows, every layer) with attention and MLP in every layer.  Weights and caches are
+    seeded device-side normal draws (unit-scale outputs); nothing is planted, the
+    selection is whatever the random scores give."""
+    cfg = cfg.with_(n_layers=n_layers, n_score_layers=min(2, n_layers))
+    lc = pipeline.layer_cfg(cfg)
+    dt = lc.torch_dtype
+    gen = torch.Generator(device=device)
+    gen.manual_seed(1234 + cfg.seed)
+    hq, hkv, d, hid = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.hidden
+    n, qn = cfg.n_ctx, cfg.n_query
+
+    def normal(*shape, scale=1.0):
+        return (torch.randn(shape, generator=gen, device=device) * scale).to(dt)
+
+    layers = []
+    for _ in range(n_layers):
+        L = dict(k_nope=normal(n, hkv, d), k_cache=torch.zeros((n + qn, hkv, d), dtype=dt,
+                                                               device=device),
+                 v_cache=torch.zeros((n + qn, hkv, d), dtype=dt, device=device),
+                 w_in=torch.ones(hid, dtype=dt, device=device),
+                 w_post=torch.ones(hid, dtype=dt, device=device),
+                 wq=normal(hq * d, hid, scale=1.5 * hid ** -0.5),
+                 wk=normal(hkv * d, hid, scale=1.5 * hid ** -0.5),
+                 wv=normal(hkv * d, hid, scale=hid ** -0.5),
+                 wo=normal(hid, hq * d, scale=(hq * d) ** -0.5),
+                 w_gate=normal(inter, hid, scale=1.5 * hid ** -0.5),
+                 w_up=normal(inter, hid, scale=hid ** -0.5),
+                 w_down=normal(hid, inter, scale=inter ** -0.5))
+        L["v_cache"][:n] = normal(n, hkv, d)
+        layers.append(L)
+    embed = normal(n + qn, hid)
+    cr = model.CarriedRows(cfg, inter, eps, device)
+    cr.run(embed, layers)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        h = cr.run(embed, layers)
+    torch.cuda.synchronize()
+    per_pass = (time.perf_counter() - t0) / steps
+    finite = bool(torch.isfinite(h.float()).all())
+    # the glue calls of one Stage II layer, one by one
+    m = cr.m
+    L = layers[0]
+    x, hbuf, g, attn = cr.x[:m], cr.h[:m], cr.g[:m], cr.attn[:m].view(m, -1)
+    calls = {
+        "rmsnorm_rows": (lambda: api.pkv_rmsnorm_rows(hbuf, None, L["w_in"], eps, x),
+                         2.0 * m * hid * 2, "hbm"),
+        "o_proj+residual": (lambda: api.pkv_linear_rows(attn, L["wo"], hbuf, hbuf, ws=cr.ws),
+                            2.0 * m * hid * hq * d, "mfma"),
+        "swiglu_rows": (lambda: api.pkv_swiglu_rows(x, L["w_gate"], L["w_up"], g, ws=cr.ws),
+                        4.0 * m * hid * inter, "mfma"),
+        "down_proj+residual": (lambda: api.pkv_linear_rows(g, L["w_down"], hbuf, hbuf,
+                                                           ws=cr.ws),
+                               2.0 * m * hid * inter, "mfma"),
+    }
+    glue = {}
+    for name, (fn, work, bound) in calls.items():
+        t = time_calls(fn, 5, batch=4)
+        glue[name] = {"us": round(t * 1e6, 1), "bound": bound}
+        if bound == "hbm":
+            glue[name]["GB/s"] = round(work / t / 1e9, 1)
+            glue[name]["frac"] = round(work / t / 1e9 / PEAK_HBM_GBS, 4)
+        else:
+            glue[name]["TFLOP/s"] = round(work / t / 1e12, 2)
+            glue[name]["frac"] = round(work / t / 1e12 / PEAK_BF16_TFLOPS, 4)
+    return {"layers": n_layers, "n_score_layers": cfg.n_score_layers, "mlp_width": inter,
+            "rows_stage2": m, "rows_stage1": qn, "ms_per_pass": round(per_pass * 1e3, 3),
+            "ms_per_layer_stage2_est": round(sum(v["us"] for v in glue.values()) * 1e-3, 3),
+            "recomputed_tokens_per_s": round(m * n_layers / per_pass, 1),
+            "output_finite": finite, "data": "synthetic (device-side seeded normal draws)",
+            "glue": glue}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -191,6 +271,9 @@ def main():
                          "topk_select, gather_qkv_proj, scatter_kv, sparse_row_attn; or "
                          "copy = a plain 1 GiB device copy that calibrates the HBM counters")
     ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--model-layers", type=int, default=4,
+                    help="layers of the carried-hidden-state model timed after the steps "
+                         "(0 = skip); bf16 configurations with head_dim 128 only")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -321,6 +404,10 @@ def main():
                      "flops_per_launch": flops, "avg_launch_s": t_attn},
         "breakdown": breakdown,
     }
+    if args.model_layers > 0 and cfg.dtype == "bf16":
+        del layers, sr
+        torch.cuda.empty_cache()
+        result["carried_model"] = carried_model(cfg, device, args.model_layers)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg.with_(n_layers=1, n_score_layers=1))
     print(json.dumps(result))
