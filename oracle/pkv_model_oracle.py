@@ -85,7 +85,8 @@ def prophetkv_model(embed, layers, n_query, k, n_score_layers,
     ``embed [N + Qn, hid]``: the layer-0 hidden state of every prompt token (context
     then query).  ``layers``: dicts with the precomputed position-free chunk caches
     ``k_nope, v [N, Hkv, D]`` of that layer and its weights ``w_in, wq, wk, wv, wo,
-    w_post, w_gate, w_up, w_down``.
+    w_post, w_gate, w_up, w_down``; optional ``bq, bk, bv`` (projection biases) and
+    ``q_norm, k_norm`` (per-head RMS-norm gains, with the block's ``eps``).
 
     Stage I (Sec. 4.2): only the Qn query rows go through the first
     ``n_score_layers`` layers; in each, their attention to the restored context keys
@@ -111,9 +112,10 @@ def prophetkv_model(embed, layers, n_query, k, n_score_layers,
         """One layer for the gathered rows ``h [m, hid]`` at positions ``rows``."""
         l = layers[li]
         x = rmsnorm_rows(h, None, l["w_in"], eps, dtype)
-        q, k_new, v_new = O.project_qkv_rows(x, np.arange(len(rows)), rows, l["wq"], l["wk"],
-                                             l["wv"], n_q_heads, n_kv_heads, head_dim,
-                                             theta, dtype)
+        q, k_new, v_new = O.project_qkv_rows(
+            x, np.arange(len(rows)), rows, l["wq"], l["wk"], l["wv"], n_q_heads, n_kv_heads,
+            head_dim, theta, dtype, bq=l.get("bq"), bk=l.get("bk"), bv=l.get("bv"),
+            q_norm=l.get("q_norm"), k_norm=l.get("k_norm"), norm_eps=eps)
         alpha = None
         if want_score:   # the rows are exactly the query rows here
             alpha = O.query_score(q, k_rope[li])

@@ -161,22 +161,39 @@ def rope_restore(k_nope, pos, theta: float, dtype: str):
 
 def project_qkv_rows(hidden, rows, row_pos, wq, wk, wv,
                      n_q_heads: int, n_kv_heads: int, head_dim: int,
-                     theta: float, dtype: str):
+                     theta: float, dtype: str, bq=None, bk=None, bv=None,
+                     q_norm=None, k_norm=None, norm_eps: float = 1e-6):
     """Q, K, V for the hidden rows ``rows`` at rotary positions ``row_pos``.
 
     ``hidden [tokens, hid]``, ``wq [Hq*D, hid]``, ``wk, wv [Hkv*D, hid]``.
     Returns ``q [m, Hq, D]``, ``k [m, Hkv, D]``, ``v [m, Hkv, D]``, each
     rounded to the storage dtype after the rotation (V is not rotated).
+
+    Variants of the public model families the paper evaluates besides Llama
+    (Sec. 5.1; the paper itself does not describe them): ``bq, bk, bv`` are
+    additive biases of the three projections (Qwen2.5); ``q_norm, k_norm [D]``
+    are the gains of an RMS normalisation over head_dim applied to every head of
+    Q and of K after the projection and before the rotation (Qwen3).  Everything
+    up to the single rounding at the end is exact arithmetic here.
     """
     hidden = np.asarray(hidden, dtype=np.float64)
     rows = np.asarray(rows, dtype=np.int64)
     m = rows.shape[0]
     xr = hidden[rows, :]                                        # [m, hid]
-    q = (xr @ np.asarray(wq, np.float64).T).reshape(m, n_q_heads, head_dim)
-    k = (xr @ np.asarray(wk, np.float64).T).reshape(m, n_kv_heads, head_dim)
-    v = (xr @ np.asarray(wv, np.float64).T).reshape(m, n_kv_heads, head_dim)
-    q = rope_rotate(q, row_pos, theta)
-    k = rope_rotate(k, row_pos, theta)
+
+    def proj(w, b, heads, gain):
+        y = xr @ np.asarray(w, np.float64).T
+        if b is not None:
+            y = y + np.asarray(b, np.float64)[None, :]
+        y = y.reshape(m, heads, head_dim)
+        if gain is not None:
+            ms = (y * y).mean(axis=2, keepdims=True)
+            y = y / np.sqrt(ms + norm_eps) * np.asarray(gain, np.float64)[None, None, :]
+        return y
+
+    q = rope_rotate(proj(wq, bq, n_q_heads, q_norm), row_pos, theta)
+    k = rope_rotate(proj(wk, bk, n_kv_heads, k_norm), row_pos, theta)
+    v = proj(wv, bv, n_kv_heads, None)
     return (round_to_storage(q, dtype), round_to_storage(k, dtype),
             round_to_storage(v, dtype))
 

@@ -75,11 +75,14 @@ def torch_forward(embed, layers, hq, hkv, d, theta, eps):
     hs, ks, vs = [], [], []
     for l in layers:
         t = {k: torch.from_numpy(np.asarray(v, np.float64)) for k, v in l.items()
-             if k.startswith("w")}
+             if k[0] in "wbqk" and k not in ("k_nope",)}
         x = F.rms_norm(h, (h.shape[1],), t["w_in"], eps)
-        q = F.linear(x, t["wq"]).view(n, hq, d)
-        k = F.linear(x, t["wk"]).view(n, hkv, d)
-        v = F.linear(x, t["wv"]).view(n, hkv, d)
+        q = F.linear(x, t["wq"], t.get("bq")).view(n, hq, d)
+        k = F.linear(x, t["wk"], t.get("bk")).view(n, hkv, d)
+        v = F.linear(x, t["wv"], t.get("bv")).view(n, hkv, d)
+        if "q_norm" in t:       # per-head RMS norm before the rotation
+            q = F.rms_norm(q, (d,), t["q_norm"], eps)
+            k = F.rms_norm(k, (d,), t["k_norm"], eps)
         ks.append(k.numpy().copy())
         vs.append(v.numpy().copy())
         qr, kr = torch_rope(q, pos, theta), torch_rope(k, pos, theta)
@@ -95,7 +98,7 @@ def torch_forward(embed, layers, hq, hkv, d, theta, eps):
     return hs, ks, vs
 
 
-def tiny_model(seed, n_ctx, n_query, hid, inter, hq, hkv, d, n_layers):
+def tiny_model(seed, n_ctx, n_query, hid, inter, hq, hkv, d, n_layers, variant="llama"):
     g = rng(seed)
     embed = g.standard_normal((n_ctx + n_query, hid))
     layers = []
@@ -106,14 +109,21 @@ def tiny_model(seed, n_ctx, n_query, hid, inter, hq, hkv, d, n_layers):
             wv=g.standard_normal((hkv * d, hid)) * 0.2, wo=g.standard_normal((hid, hq * d)) * 0.2,
             w_gate=g.standard_normal((inter, hid)) * 0.2, w_up=g.standard_normal((inter, hid)) * 0.2,
             w_down=g.standard_normal((hid, inter)) * 0.2))
+        if variant == "qkv-bias":
+            layers[-1].update(bq=g.standard_normal(hq * d), bk=g.standard_normal(hkv * d),
+                              bv=g.standard_normal(hkv * d))
+        elif variant == "qk-norm":
+            layers[-1].update(q_norm=1 + 0.3 * g.standard_normal(d),
+                              k_norm=1 + 0.3 * g.standard_normal(d))
     return embed, layers
 
 
+@pytest.mark.parametrize("variant", ["llama", "qkv-bias", "qk-norm"])
 @pytest.mark.parametrize("k_sel", [0, 7, 40])
-def test_exact_cache_reproduces_the_ordinary_forward_for_any_selection(k_sel):
+def test_exact_cache_reproduces_the_ordinary_forward_for_any_selection(k_sel, variant):
     n_ctx, n_query, hid, inter, hq, hkv, d, L = 40, 5, 32, 48, 4, 2, 8, 3
     theta, eps = 10000.0, 1e-6
-    embed, layers = tiny_model(3, n_ctx, n_query, hid, inter, hq, hkv, d, L)
+    embed, layers = tiny_model(3, n_ctx, n_query, hid, inter, hq, hkv, d, L, variant)
     hs, ks, vs = torch_forward(embed, layers, hq, hkv, d, theta, eps)
     for l, k, v in zip(layers, ks, vs):      # one chunk: its cache is the true one
         l["k_nope"], l["v"] = k[:n_ctx], v[:n_ctx]

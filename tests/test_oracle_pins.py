@@ -274,6 +274,75 @@ def test_projection_gathers_the_named_rows():
         assert np.array_equal(u, v)
 
 
+def _proj_inputs(seed, hq=4, hkv=2, d=8, hid=24, m=6):
+    g = rng(seed)
+    x = g.standard_normal((m, hid))
+    w = [g.standard_normal((hq * d, hid)), g.standard_normal((hkv * d, hid)),
+         g.standard_normal((hkv * d, hid))]
+    b = [g.standard_normal(hq * d), g.standard_normal(hkv * d), g.standard_normal(hkv * d)]
+    pos = np.array([0, 3, 4, 100, 101, 7])[:m]
+    return x, w, b, pos, (hq, hkv, d)
+
+
+def test_projection_bias_equals_an_augmented_weight_column():
+    """x W^T + b = [x, 1] [W, b]^T: the biased projection must equal the unbiased one
+    on inputs with a constant 1 appended and the bias as one more weight column."""
+    x, w, b, pos, (hq, hkv, d) = _proj_inputs(41)
+    m = x.shape[0]
+    got = O.project_qkv_rows(x, np.arange(m), pos, *w, hq, hkv, d, 1e4, "f64",
+                             bq=b[0], bk=b[1], bv=b[2])
+    x1 = np.concatenate([x, np.ones((m, 1))], axis=1)
+    w1 = [np.concatenate([wi, bi[:, None]], axis=1) for wi, bi in zip(w, b)]
+    want = O.project_qkv_rows(x1, np.arange(m), pos, *w1, hq, hkv, d, 1e4, "f64")
+    for u, v in zip(got, want):
+        assert np.allclose(u, v, rtol=1e-12, atol=1e-12)
+    # and against torch's biased linear layer for V (no rotation there)
+    lin = torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(w[2]),
+                                     torch.from_numpy(b[2])).numpy()
+    assert np.allclose(got[2], lin.reshape(m, hkv, d), rtol=1e-13, atol=1e-13)
+    # a bias on one projection leaves the other two alone
+    only_q = O.project_qkv_rows(x, np.arange(m), pos, *w, hq, hkv, d, 1e4, "f64", bq=b[0])
+    plain = O.project_qkv_rows(x, np.arange(m), pos, *w, hq, hkv, d, 1e4, "f64")
+    assert np.array_equal(only_q[1], plain[1]) and np.array_equal(only_q[2], plain[2])
+    assert not np.allclose(only_q[0], plain[0])
+
+
+def test_projection_head_norm_against_torch_rms_norm_and_its_invariances():
+    x, w, b, pos, (hq, hkv, d) = _proj_inputs(42)
+    m = x.shape[0]
+    g = rng(43)
+    gq, gk = g.standard_normal(d), g.standard_normal(d)
+    eps = 1e-6
+    q, k, v = O.project_qkv_rows(x, np.arange(m), pos, *w, hq, hkv, d, 1e4, "f64",
+                                 q_norm=gq, k_norm=gk, norm_eps=eps)
+    lin = lambda wi: torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(wi))
+    nq = torch.nn.functional.rms_norm(lin(w[0]).reshape(m, hq, d), (d,),
+                                      torch.from_numpy(gq), eps).numpy()
+    nk = torch.nn.functional.rms_norm(lin(w[1]).reshape(m, hkv, d), (d,),
+                                      torch.from_numpy(gk), eps).numpy()
+    assert np.allclose(q, complex_rope(nq, pos, 1e4), rtol=1e-12, atol=1e-12)
+    assert np.allclose(k, complex_rope(nk, pos, 1e4), rtol=1e-12, atol=1e-12)
+    assert np.allclose(v, lin(w[2]).numpy().reshape(m, hkv, d), rtol=1e-13, atol=1e-13)
+    # with eps = 0 and unit gains every head of q and k has norm sqrt(D) at any position,
+    # and scaling the hidden rows changes nothing but v
+    ones = np.ones(d)
+    q1, k1, v1 = O.project_qkv_rows(x, np.arange(m), pos, *w, hq, hkv, d, 1e4, "f64",
+                                    q_norm=ones, k_norm=ones, norm_eps=0.0)
+    assert np.allclose(np.linalg.norm(q1, axis=2), np.sqrt(d), rtol=1e-12)
+    assert np.allclose(np.linalg.norm(k1, axis=2), np.sqrt(d), rtol=1e-12)
+    q2, k2, v2 = O.project_qkv_rows(7.5 * x, np.arange(m), pos, *w, hq, hkv, d, 1e4, "f64",
+                                    q_norm=ones, k_norm=ones, norm_eps=0.0)
+    assert np.allclose(q1, q2, rtol=1e-12, atol=1e-12)
+    assert np.allclose(k1, k2, rtol=1e-12, atol=1e-12)
+    assert np.allclose(7.5 * v1, v2, rtol=1e-12, atol=1e-12)
+    # the norm comes BEFORE the rotation: norm then rotate != rotate then norm only through
+    # the gain, so with a non-constant gain the two orders differ while with unit gain they agree
+    plain = O.project_qkv_rows(x, np.arange(m), pos, *w, hq, hkv, d, 1e4, "f64")
+    after = plain[0] / np.sqrt((plain[0] ** 2).mean(axis=2, keepdims=True))
+    assert np.allclose(q1, after, rtol=1e-12, atol=1e-12)
+    assert not np.allclose(q[3], after[3] * gq, rtol=1e-3, atol=1e-3)
+
+
 # ---------------------------------------------------------------- scatter
 
 def test_scatter_replaces_only_the_named_rows():
