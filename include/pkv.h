@@ -169,6 +169,38 @@ pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg,
                                void* stream);
 
 /*
+ * Step 4a for the other public model families the paper evaluates (Sec. 5.1 names
+ * Qwen models besides Llama; the paper does not describe their blocks, so these
+ * are the public architectures, not something the paper defines):
+ *   bq, bk, bv      additive biases of the three projections ([Hq*D], [Hkv*D],
+ *                   [Hkv*D], element type cfg->dtype), each may be NULL;
+ *   q_norm, k_norm  gains [D] of an RMS normalisation over head_dim applied to
+ *                   every head of Q and of K after projection and bias and BEFORE
+ *                   the rotation: y = x / sqrt(mean(x^2) + norm_eps) * gain.
+ *                   Both or neither.  V is never normalised.
+ * Everything runs in fp32 on the fp32 accumulators; there is still exactly one
+ * rounding to cfg->dtype, after the rotation.  `variant` is a HOST pointer read
+ * during the call (NULL = plain pkv_gather_qkv_proj); the pointers inside it are
+ * device pointers.  Same scratch, errors and no-op rules as pkv_gather_qkv_proj.
+ */
+typedef struct {
+    const void* bq;
+    const void* bk;
+    const void* bv;
+    const void* q_norm;
+    const void* k_norm;
+    float norm_eps;
+} pkv_proj_variant;
+
+pkv_status pkv_gather_qkv_proj_ex(const pkv_layer_cfg* cfg,
+                                  const void* hidden, const int32_t* row_idx,
+                                  const int32_t* row_pos, const void* wq,
+                                  const void* wk, const void* wv,
+                                  const pkv_proj_variant* variant,
+                                  void* q_out, void* k_out, void* v_out, int64_t m,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Step 4b - cache update (paper: Algorithm 1 "Update layer-wise KV cache":
  * rows in T_p take the recomputed K/V, all other rows are reused as they
  * are; the user-query K/V are appended after the context).

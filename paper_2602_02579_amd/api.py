@@ -18,8 +18,8 @@ import torch
 
 __all__ = ["LayerCfg", "PkvError", "load_library", "library_path",
            "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
-           "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
-           "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
+           "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_scatter_kv",
+           "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
            "pkv_glue_workspace_bytes",
            "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
            "EXPORTED_SYMBOLS"]
@@ -30,7 +30,7 @@ CALL_GATHER_QKV_PROJ, CALL_SCATTER_KV, CALL_SPARSE_ROW_ATTN = 4, 5, 6
 
 EXPORTED_SYMBOLS = [
     "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
-    "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
+    "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_scatter_kv", "pkv_sparse_row_attn",
     "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
     "pkv_glue_workspace_bytes",
     "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
@@ -41,6 +41,12 @@ class PkvError(RuntimeError):
     def __init__(self, call: str, status: int, text: str):
         super().__init__(f"{call} failed: status {status} ({text})")
         self.status = status
+
+
+class _CVariant(ctypes.Structure):
+    _fields_ = [("bq", ctypes.c_void_p), ("bk", ctypes.c_void_p), ("bv", ctypes.c_void_p),
+                ("q_norm", ctypes.c_void_p), ("k_norm", ctypes.c_void_p),
+                ("norm_eps", ctypes.c_float)]
 
 
 class _CCfg(ctypes.Structure):
@@ -99,6 +105,9 @@ def load_library() -> ctypes.CDLL:
     lib.pkv_topk_select.argtypes = [f32p, i64, i64, i32p, vp, ctypes.c_size_t, vp]
     lib.pkv_gather_qkv_proj.argtypes = [cfgp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp,
                                         i64, vp, ctypes.c_size_t, vp]
+    lib.pkv_gather_qkv_proj_ex.argtypes = [cfgp, vp, i32p, i32p, vp, vp, vp,
+                                           ctypes.POINTER(_CVariant), vp, vp, vp,
+                                           i64, vp, ctypes.c_size_t, vp]
     lib.pkv_scatter_kv.argtypes = [cfgp, vp, vp, i32p, vp, vp, i64, i64, vp]
     lib.pkv_sparse_row_attn.argtypes = [cfgp, vp, vp, vp, i32p, vp, f32p, i64, i64,
                                         ctypes.c_float, vp, ctypes.c_size_t, vp]
@@ -112,8 +121,8 @@ def load_library() -> ctypes.CDLL:
     lib.pkv_glue_workspace_bytes.argtypes = [i32, i64, i64, i64]
     lib.pkv_glue_workspace_bytes.restype = ctypes.c_size_t
     for name in ("pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
-                 "pkv_gather_qkv_proj", "pkv_scatter_kv", "pkv_sparse_row_attn",
-                 "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows",
+                 "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_scatter_kv",
+                 "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows",
                  "pkv_swiglu_rows"):
         getattr(lib, name).restype = ctypes.c_int
     lib.pkv_workspace_bytes.argtypes = [ctypes.c_int, cfgp, i64, i64]
@@ -212,15 +221,8 @@ def pkv_topk_select(score: torch.Tensor, k: int, idx_out: torch.Tensor,
         _ptr(idx_out, torch.int32, "idx_out"), wp, wb, _stream()))
 
 
-def pkv_gather_qkv_proj(cfg: LayerCfg, hidden: torch.Tensor,
-                        row_idx: Optional[torch.Tensor], row_pos: torch.Tensor,
-                        wq: Optional[torch.Tensor], wk: Optional[torch.Tensor],
-                        wv: Optional[torch.Tensor], q_out: Optional[torch.Tensor],
-                        k_out: Optional[torch.Tensor],
-                        v_out: Optional[torch.Tensor],
-                        ws: Optional[torch.Tensor] = None) -> None:
+def _check_proj_args(cfg, hidden, row_idx, row_pos, wq, wk, wv, q_out, k_out, v_out):
     m = row_pos.shape[0]
-    dt = cfg.torch_dtype
     if hidden.dim() != 2 or hidden.shape[1] != cfg.hidden:
         raise ValueError("hidden must be [rows, hidden]")
     if row_idx is not None and tuple(row_idx.shape) != (m,):
@@ -235,6 +237,18 @@ def pkv_gather_qkv_proj(cfg: LayerCfg, hidden: torch.Tensor,
                            (wv, cfg.n_kv_heads, "wv")):
         if t is not None and tuple(t.shape) != (heads * cfg.head_dim, cfg.hidden):
             raise ValueError(f"{name} must be [heads*D, hidden]")
+    return m
+
+
+def pkv_gather_qkv_proj(cfg: LayerCfg, hidden: torch.Tensor,
+                        row_idx: Optional[torch.Tensor], row_pos: torch.Tensor,
+                        wq: Optional[torch.Tensor], wk: Optional[torch.Tensor],
+                        wv: Optional[torch.Tensor], q_out: Optional[torch.Tensor],
+                        k_out: Optional[torch.Tensor],
+                        v_out: Optional[torch.Tensor],
+                        ws: Optional[torch.Tensor] = None) -> None:
+    m = _check_proj_args(cfg, hidden, row_idx, row_pos, wq, wk, wv, q_out, k_out, v_out)
+    dt = cfg.torch_dtype
     wp, wb = _ws(ws)
     c = cfg._c()
     _check("pkv_gather_qkv_proj", load_library().pkv_gather_qkv_proj(
@@ -242,6 +256,42 @@ def pkv_gather_qkv_proj(cfg: LayerCfg, hidden: torch.Tensor,
         _ptr(row_pos, torch.int32, "row_pos"), _ptr(wq, dt, "wq"), _ptr(wk, dt, "wk"),
         _ptr(wv, dt, "wv"), _ptr(q_out, dt, "q_out"), _ptr(k_out, dt, "k_out"),
         _ptr(v_out, dt, "v_out"), m, wp, wb, _stream()))
+
+
+def pkv_gather_qkv_proj_ex(cfg: LayerCfg, hidden: torch.Tensor,
+                           row_idx: Optional[torch.Tensor], row_pos: torch.Tensor,
+                           wq: Optional[torch.Tensor], wk: Optional[torch.Tensor],
+                           wv: Optional[torch.Tensor], q_out: Optional[torch.Tensor],
+                           k_out: Optional[torch.Tensor], v_out: Optional[torch.Tensor],
+                           ws: Optional[torch.Tensor] = None, *,
+                           bq: Optional[torch.Tensor] = None,
+                           bk: Optional[torch.Tensor] = None,
+                           bv: Optional[torch.Tensor] = None,
+                           q_norm: Optional[torch.Tensor] = None,
+                           k_norm: Optional[torch.Tensor] = None,
+                           norm_eps: float = 1e-6) -> None:
+    m = _check_proj_args(cfg, hidden, row_idx, row_pos, wq, wk, wv, q_out, k_out, v_out)
+    dt = cfg.torch_dtype
+    for t, n, name in ((bq, cfg.n_q_heads, "bq"), (bk, cfg.n_kv_heads, "bk"),
+                       (bv, cfg.n_kv_heads, "bv")):
+        if t is not None and tuple(t.shape) != (n * cfg.head_dim,):
+            raise ValueError(f"{name} must be [heads*D]")
+    for t, name in ((q_norm, "q_norm"), (k_norm, "k_norm")):
+        if t is not None and tuple(t.shape) != (cfg.head_dim,):
+            raise ValueError(f"{name} must be [D]")
+
+    def raw(t, name):
+        p = _ptr(t, dt, name)
+        return None if p is None else p.value
+    var = _CVariant(raw(bq, "bq"), raw(bk, "bk"), raw(bv, "bv"), raw(q_norm, "q_norm"),
+                    raw(k_norm, "k_norm"), float(norm_eps))
+    wp, wb = _ws(ws)
+    c = cfg._c()
+    _check("pkv_gather_qkv_proj_ex", load_library().pkv_gather_qkv_proj_ex(
+        ctypes.byref(c), _ptr(hidden, dt, "hidden"), _ptr(row_idx, torch.int32, "row_idx"),
+        _ptr(row_pos, torch.int32, "row_pos"), _ptr(wq, dt, "wq"), _ptr(wk, dt, "wk"),
+        _ptr(wv, dt, "wv"), ctypes.byref(var), _ptr(q_out, dt, "q_out"),
+        _ptr(k_out, dt, "k_out"), _ptr(v_out, dt, "v_out"), m, wp, wb, _stream()))
 
 
 def pkv_scatter_kv(cfg: LayerCfg, k_new: torch.Tensor, v_new: torch.Tensor,

@@ -19,49 +19,94 @@ namespace {
 // is one (row, pair index i) and produces output elements i and i + D/2, so
 // the rotation is local to the thread.
 // ---------------------------------------------------------------------------
+// Block variants: bias[3] are additive biases of the three projections, gain[2] the
+// gains of an RMS norm over head_dim applied to every head of Q and K before the
+// rotation (null = absent).  The norm needs the whole head of a row: the squares go
+// through LDS and every work item adds up its row's D/2 partial sums in a fixed order.
+struct ProjExtra {
+    const void* bias[3];
+    const void* gain[2];
+    float eps;
+};
+
 template <typename T>
 __global__ __launch_bounds__(256) void qkv_proj_generic(
     const T* __restrict__ hidden, const int32_t* __restrict__ row_idx,
     const int32_t* __restrict__ row_pos, const T* __restrict__ wq,
     const T* __restrict__ wk, const T* __restrict__ wv, T* __restrict__ q_out,
     T* __restrict__ k_out, T* __restrict__ v_out, int m, int hq, int hkv, int d,
-    int hid, RopeTable tab) {
+    int hid, RopeTable tab, ProjExtra ex) {
     constexpr int V = Vec16<T>::N;
+    constexpr int kMaxItems = 16 * kMaxHalfDim / 256;   // work items per thread
     typedef typename Vec16<T>::type vec_t;
+    __shared__ float s_sq[16 * kMaxHalfDim];
     const int head = blockIdx.y;  // [0,hq) Q, [hq,hq+hkv) K, [hq+hkv,hq+2hkv) V
     const T* w;
     T* out;
-    int heads_out, head_local;
-    bool rotate;
+    int heads_out, head_local, mat;
     if (head < hq) {
-        w = wq; out = q_out; heads_out = hq; head_local = head; rotate = true;
+        w = wq; out = q_out; heads_out = hq; head_local = head; mat = 0;
     } else if (head < hq + hkv) {
-        w = wk; out = k_out; heads_out = hkv; head_local = head - hq; rotate = true;
+        w = wk; out = k_out; heads_out = hkv; head_local = head - hq; mat = 1;
     } else {
-        w = wv; out = v_out; heads_out = hkv; head_local = head - hq - hkv; rotate = false;
+        w = wv; out = v_out; heads_out = hkv; head_local = head - hq - hkv; mat = 2;
     }
-    if (out == nullptr) return;
+    if (out == nullptr) return;   // uniform over the block
+    const bool rotate = mat != 2;
+    const T* bias = static_cast<const T*>(ex.bias[mat]);
+    const T* gain = mat != 2 ? static_cast<const T*>(ex.gain[mat]) : nullptr;
     const int half = d / 2;
     const int row0 = blockIdx.x * 16;
-    for (int item = threadIdx.x; item < 16 * half; item += 256) {
+    float va[kMaxItems], vb[kMaxItems];
+#pragma unroll
+    for (int it = 0; it < kMaxItems; ++it) {
+        const int item = threadIdx.x + it * 256;
+        va[it] = vb[it] = 0.f;
+        if (item >= 16 * half) continue;
+        const int r = row0 + item / half;
+        const int i = item % half;
+        if (r < m) {
+            const int64_t src_row = row_idx ? row_idx[r] : r;
+            const T* x = hidden + src_row * hid;
+            const T* wa = w + ((int64_t)head_local * d + i) * hid;
+            const T* wb = wa + (int64_t)half * hid;
+            float a = 0.f, b = 0.f;
+            for (int c = 0; c < hid; c += V) {
+                const vec_t xv = *reinterpret_cast<const vec_t*>(x + c);
+                const vec_t av = *reinterpret_cast<const vec_t*>(wa + c);
+                const vec_t bv = *reinterpret_cast<const vec_t*>(wb + c);
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    const float xf = Elem<T>::to_f32(xv[j]);
+                    a += xf * Elem<T>::to_f32(av[j]);
+                    b += xf * Elem<T>::to_f32(bv[j]);
+                }
+            }
+            if (bias) {
+                a += Elem<T>::load(bias + head_local * d + i);
+                b += Elem<T>::load(bias + head_local * d + i + half);
+            }
+            va[it] = a;
+            vb[it] = b;
+        }
+        if (gain) s_sq[item] = va[it] * va[it] + vb[it] * vb[it];
+    }
+    if (gain) __syncthreads();    // uniform: gain depends on the block's head only
+#pragma unroll
+    for (int it = 0; it < kMaxItems; ++it) {
+        const int item = threadIdx.x + it * 256;
+        if (item >= 16 * half) continue;
         const int r = row0 + item / half;
         const int i = item % half;
         if (r >= m) continue;
-        const int64_t src_row = row_idx ? row_idx[r] : r;
-        const T* x = hidden + src_row * hid;
-        const T* wa = w + ((int64_t)head_local * d + i) * hid;
-        const T* wb = wa + (int64_t)half * hid;
-        float a = 0.f, b = 0.f;
-        for (int c = 0; c < hid; c += V) {
-            const vec_t xv = *reinterpret_cast<const vec_t*>(x + c);
-            const vec_t av = *reinterpret_cast<const vec_t*>(wa + c);
-            const vec_t bv = *reinterpret_cast<const vec_t*>(wb + c);
-#pragma unroll
-            for (int j = 0; j < V; ++j) {
-                const float xf = Elem<T>::to_f32(xv[j]);
-                a += xf * Elem<T>::to_f32(av[j]);
-                b += xf * Elem<T>::to_f32(bv[j]);
-            }
+        float a = va[it], b = vb[it];
+        if (gain) {
+            float ss = 0.f;
+            const float* sq = s_sq + (item / half) * half;
+            for (int t = 0; t < half; ++t) ss += sq[t];
+            const float rn = 1.0f / sqrtf(ss / (float)d + ex.eps);
+            a = a * rn * Elem<T>::load(gain + i);
+            b = b * rn * Elem<T>::load(gain + i + half);
         }
         float ra = a, rb = b;
         if (rotate) {
@@ -248,13 +293,22 @@ size_t gather_qkv_proj_ws_bytes(const pkv_layer_cfg& cfg, int64_t m) {
 pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
                                   const int32_t* row_idx, const int32_t* row_pos,
                                   const void* wq, const void* wk, const void* wv,
-                                  void* q_out, void* k_out, void* v_out,
-                                  int64_t m, void* ws, hipStream_t st) {
+                                  const pkv_proj_variant* var, void* q_out, void* k_out,
+                                  void* v_out, int64_t m, void* ws, hipStream_t st) {
     if (m == 0) return PKV_OK;
+    ProjExtra ex = {};
+    if (var) {
+        ex.bias[0] = var->bq; ex.bias[1] = var->bk; ex.bias[2] = var->bv;
+        ex.gain[0] = var->q_norm; ex.gain[1] = var->k_norm;
+        ex.eps = var->norm_eps;
+    }
+    const bool extra = ex.bias[0] || ex.bias[1] || ex.bias[2] || ex.gain[0] || ex.gain[1];
     RopeTable tab;
     fill_rope_table(&tab, cfg.head_dim, (double)cfg.rope_theta);
     const int hq = cfg.n_q_heads, hkv = cfg.n_kv_heads;
-    if (mfma_proj_supported(cfg)) {
+    // the variants are built into the 256 x 256 tile kernel and the plain kernel; the older
+    // 256 x 128 MFMA kernel (head_dim 64, odd head counts) does not have them
+    if (mfma_proj_supported(cfg) && (!extra || proj_dma128_supported(cfg, m))) {
         const int d = cfg.head_dim, half = d / 2;
         float2* cs = (float2*)ws;
         const int64_t n_tab = m * half;
@@ -267,6 +321,9 @@ pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
         p.out[0] = (bf16_t*)q_out; p.out[1] = (bf16_t*)k_out; p.out[2] = (bf16_t*)v_out;
         p.cs = cs;
         p.m = (int)m; p.hid = cfg.hidden; p.hq = hq; p.hkv = hkv;
+        for (int i = 0; i < 3; ++i) p.bias[i] = (const bf16_t*)ex.bias[i];
+        for (int i = 0; i < 2; ++i) p.norm_w[i] = (const bf16_t*)ex.gain[i];
+        p.norm_eps = ex.eps;
         if (proj_dma128_supported(cfg, m)) {
             const int tq = q_out ? hq * d / kProjDmaTile : 0;
             const int tkv = k_out ? hkv * d / kProjDmaTile : 0;
@@ -296,13 +353,13 @@ pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
                            (const bf16_t*)hidden, row_idx, row_pos,
                            (const bf16_t*)wq, (const bf16_t*)wk, (const bf16_t*)wv,
                            (bf16_t*)q_out, (bf16_t*)k_out, (bf16_t*)v_out, (int)m,
-                           hq, hkv, cfg.head_dim, cfg.hidden, tab);
+                           hq, hkv, cfg.head_dim, cfg.hidden, tab, ex);
     } else {
         hipLaunchKernelGGL(qkv_proj_generic<float>, grid, dim3(256), 0, st,
                            (const float*)hidden, row_idx, row_pos,
                            (const float*)wq, (const float*)wk, (const float*)wv,
                            (float*)q_out, (float*)k_out, (float*)v_out, (int)m, hq,
-                           hkv, cfg.head_dim, cfg.hidden, tab);
+                           hkv, cfg.head_dim, cfg.hidden, tab, ex);
     }
     return launch_status();
 }

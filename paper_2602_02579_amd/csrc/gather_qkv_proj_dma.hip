@@ -64,7 +64,8 @@ __device__ __forceinline__ void wait_vm() {
 
 __device__ __forceinline__ float silu_f32(float a) { return a / (1.f + __expf(-a)); }
 
-template <int MODE>
+// EXTRA (Q | K | V mode only): the launch has projection biases and/or per-head norm gains
+template <int MODE, bool EXTRA = false>
 __global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_tiles,
                                                        int n_tiles, int per_xcd) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -326,6 +327,9 @@ __global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_t
     }
     const int head = feat0 / D + wf;
     const bool rotate = mat != 2;
+    // block variants: bias of this head's features, gains of the head norm (Q and K only)
+    const bf16_t* bias = EXTRA && p.bias[mat] ? p.bias[mat] + head * D : nullptr;
+    const bf16_t* gain = EXTRA && mat != 2 ? p.norm_w[mat] : nullptr;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -334,6 +338,30 @@ __global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_t
             const int row = min(row0 + wt * 128 + tb * 32 + l32, p.m - 1);
             const float4* cs = reinterpret_cast<const float4*>(p.cs + (int64_t)row * (D / 2));
             unsigned char* erow = epi + (tbl * 32 + l32) * kEpiStride;
+            float rnorm = 1.f;
+            if (EXTRA) {
+                if (bias) {
+#pragma unroll
+                    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const bf16x4 bv =
+                                *reinterpret_cast<const bf16x4*>(bias + fb * 32 + 8 * j + 4 * hh);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[fb][tb][4 * j + e] += (float)bv[e];
+                        }
+                }
+                if (gain) {
+                    // the lane holds 64 of the token's 128 features, lane ^ 32 the other 64
+                    float ss = 0.f;
+#pragma unroll
+                    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) ss += acc[fb][tb][r] * acc[fb][tb][r];
+                    ss += __shfl_xor(ss, 32);
+                    rnorm = 1.0f / sqrtf(ss * (1.0f / D) + p.norm_eps);
+                }
+            }
 #pragma unroll
             for (int fbp = 0; fbp < 2; ++fbp)
 #pragma unroll
@@ -344,6 +372,15 @@ __global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_t
                     for (int e = 0; e < 4; ++e) {
                         a[e] = acc[fbp][tb][4 * j + e];
                         b[e] = acc[fbp + 2][tb][4 * j + e];
+                    }
+                    if (EXTRA && gain) {
+                        const bf16x4 ga = *reinterpret_cast<const bf16x4*>(gain + i0);
+                        const bf16x4 gb = *reinterpret_cast<const bf16x4*>(gain + i0 + D / 2);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            a[e] = a[e] * rnorm * (float)ga[e];
+                            b[e] = b[e] * rnorm * (float)gb[e];
+                        }
                     }
                     if (rotate) {
                         const float4 t0 = cs[i0 / 2], t1 = cs[i0 / 2 + 1];
@@ -403,6 +440,19 @@ __global__ __launch_bounds__(256) void proj_splitk_finish_kernel(ProjParams p) {
         const float* src = p.partial + ((int64_t)s * p.m + row) * f_total + hs * D + i;
         a += src[0];
         b += src[D / 2];
+    }
+    if (p.bias[mat]) {
+        a += (float)p.bias[mat][head * D + i];
+        b += (float)p.bias[mat][head * D + i + D / 2];
+    }
+    if (mat != 2 && p.norm_w[mat]) {
+        // a wave is exactly one (row, head): its 64 lanes hold the head's 128 features
+        float ss = a * a + b * b;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+        const float r = 1.0f / sqrtf(ss * (1.0f / D) + p.norm_eps);
+        a = a * r * (float)p.norm_w[mat][i];
+        b = b * r * (float)p.norm_w[mat][i + D / 2];
     }
     if (mat != 2) {
         const float2 t = p.cs[(int64_t)row * (D / 2) + i];
@@ -480,11 +530,11 @@ bool proj_dma128_supported(const pkv_layer_cfg& cfg, int64_t m) {
 
 namespace {
 
-template <int MODE>
+template <int MODE, bool EXTRA = false>
 pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
     static bool configured = false;
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(proj_dma_kernel<MODE>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(proj_dma_kernel<MODE, EXTRA>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
@@ -498,7 +548,7 @@ pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
     q.n_ksplit = plan_ksplit(n_tiles, p.hid / BK);
     if (q.n_ksplit > 1 && q.partial == nullptr) return PKV_ERR_WORKSPACE;
     const int per_xcd = (int)ceil_div(n_tiles * q.n_ksplit, 8);
-    hipLaunchKernelGGL(proj_dma_kernel<MODE>, dim3((unsigned)(per_xcd * 8)), dim3(256),
+    hipLaunchKernelGGL((proj_dma_kernel<MODE, EXTRA>), dim3((unsigned)(per_xcd * 8)), dim3(256),
                        kLdsBytes, st, q, n_tok_tiles, (int)n_tiles, per_xcd);
     if (q.n_ksplit > 1) {
         if (MODE == kProjRope) {
@@ -517,7 +567,8 @@ pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
 }  // namespace
 
 pkv_status launch_proj_dma128(const ProjParams& p, hipStream_t st) {
-    return launch_tiles<kProjRope>(p, st);
+    const bool extra = p.bias[0] || p.bias[1] || p.bias[2] || p.norm_w[0] || p.norm_w[1];
+    return extra ? launch_tiles<kProjRope, true>(p, st) : launch_tiles<kProjRope, false>(p, st);
 }
 
 bool linear_dma_supported(int mode, int64_t m, int64_t k_in, int64_t n_out) {

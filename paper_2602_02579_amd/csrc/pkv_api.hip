@@ -72,14 +72,20 @@ pkv_status pkv_topk_select(const float* score, int64_t n, int64_t k,
     return launch_topk_select(score, n, k, idx_out, (hipStream_t)stream);
 }
 
-pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg, const void* hidden,
-                               const int32_t* row_idx, const int32_t* row_pos,
-                               const void* wq, const void* wk, const void* wv,
-                               void* q_out, void* k_out, void* v_out, int64_t m,
-                               void* ws, size_t ws_bytes, void* stream) {
+pkv_status pkv_gather_qkv_proj_ex(const pkv_layer_cfg* cfg, const void* hidden,
+                                  const int32_t* row_idx, const int32_t* row_pos,
+                                  const void* wq, const void* wk, const void* wv,
+                                  const pkv_proj_variant* variant, void* q_out, void* k_out,
+                                  void* v_out, int64_t m, void* ws, size_t ws_bytes,
+                                  void* stream) {
     pkv_status st = check_cfg(cfg);
     if (st != PKV_OK) return st;
     if (m < 0 || m > kMaxTokens) return PKV_ERR_SHAPE;
+    if (variant) {
+        if ((variant->q_norm == nullptr) != (variant->k_norm == nullptr)) return PKV_ERR_NULL;
+        if (variant->q_norm && (!(variant->norm_eps >= 0.f) || !std::isfinite(variant->norm_eps)))
+            return PKV_ERR_SHAPE;
+    }
     if (m == 0) return PKV_OK;
     if (!hidden || !row_pos) return PKV_ERR_NULL;
     if ((k_out == nullptr) != (v_out == nullptr)) return PKV_ERR_NULL;
@@ -88,8 +94,17 @@ pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg, const void* hidden,
     if (k_out && (!wk || !wv)) return PKV_ERR_NULL;
     const size_t need = align256(gather_qkv_proj_ws_bytes(*cfg, m));
     if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
-    return launch_gather_qkv_proj(*cfg, hidden, row_idx, row_pos, wq, wk, wv, q_out,
+    return launch_gather_qkv_proj(*cfg, hidden, row_idx, row_pos, wq, wk, wv, variant, q_out,
                                   k_out, v_out, m, ws, (hipStream_t)stream);
+}
+
+pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg, const void* hidden,
+                               const int32_t* row_idx, const int32_t* row_pos,
+                               const void* wq, const void* wk, const void* wv,
+                               void* q_out, void* k_out, void* v_out, int64_t m,
+                               void* ws, size_t ws_bytes, void* stream) {
+    return pkv_gather_qkv_proj_ex(cfg, hidden, row_idx, row_pos, wq, wk, wv, nullptr, q_out,
+                                  k_out, v_out, m, ws, ws_bytes, stream);
 }
 
 pkv_status pkv_scatter_kv(const pkv_layer_cfg* cfg, const void* k_new,

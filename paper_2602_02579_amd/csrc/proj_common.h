@@ -19,6 +19,12 @@ struct ProjParams {
     // elements, w[0] (and w[1], the up matrix of the gated form); mat is always 0
     const bf16_t* residual;   // [m, n_out] or null
     int n_out;
+    // Q | K | V launches of block variants: additive bias of each projection
+    // ([heads * D] or null) and gains of the per-head RMS norm of Q and K applied before
+    // the rotation ([D] or null)
+    const bf16_t* bias[3];
+    const bf16_t* norm_w[2];
+    float norm_eps;
 };
 
 // what the tile's epilogue does with the accumulators

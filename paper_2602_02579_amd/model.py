@@ -22,6 +22,9 @@ from .pipeline import layer_cfg
 from .synth import Config, select_count
 
 BLOCK_WEIGHTS = ("w_in", "wq", "wk", "wv", "wo", "w_post", "w_gate", "w_up", "w_down")
+# block variants of the other public model families the paper evaluates (Sec. 5.1):
+# projection biases (Qwen2.5) and per-head RMS-norm gains of Q and K (Qwen3)
+VARIANT_WEIGHTS = ("bq", "bk", "bv", "q_norm", "k_norm")
 
 
 def upload_block(cfg: Config, layer: Dict[str, np.ndarray],
@@ -29,8 +32,9 @@ def upload_block(cfg: Config, layer: Dict[str, np.ndarray],
     """Host arrays of one layer (``k_nope, v`` and the block weights) -> device tensors;
     ``k_cache``/``v_cache`` get room for the query rows after the context."""
     dt = layer_cfg(cfg).torch_dtype
+    names = ("k_nope",) + BLOCK_WEIGHTS + tuple(v for v in VARIANT_WEIGHTS if v in layer)
     out = {name: torch.from_numpy(np.ascontiguousarray(layer[name])).to(dt).to(device)
-           for name in ("k_nope",) + BLOCK_WEIGHTS}
+           for name in names}
     n, qn = cfg.n_ctx, cfg.n_query
     v_cache = torch.zeros((n + qn, cfg.n_kv_heads, cfg.head_dim), dtype=dt, device=device)
     v_cache[:n] = torch.from_numpy(np.ascontiguousarray(layer["v"])).to(dt).to(device)
@@ -87,8 +91,13 @@ class CarriedRows:
         q, k_new, v_new = self.q[:cnt], self.k_new[:cnt], self.v_new[:cnt]
         attn, g = self.attn[:cnt], self.g[:cnt]
         api.pkv_rmsnorm_rows(h, None, L["w_in"], self.eps, x)
-        api.pkv_gather_qkv_proj(lc, x, None, rows, L["wq"], L["wk"], L["wv"], q, k_new, v_new,
-                                ws=ws)
+        if any(v in L for v in VARIANT_WEIGHTS):
+            api.pkv_gather_qkv_proj_ex(lc, x, None, rows, L["wq"], L["wk"], L["wv"], q, k_new,
+                                       v_new, ws=ws, norm_eps=self.eps,
+                                       **{v: L[v] for v in VARIANT_WEIGHTS if v in L})
+        else:
+            api.pkv_gather_qkv_proj(lc, x, None, rows, L["wq"], L["wk"], L["wv"], q, k_new,
+                                    v_new, ws=ws)
         if score is not None:
             api.pkv_query_score(lc, q, L["k_cache"][:self.n], self.score, accumulate=score,
                                 ws=ws)
