@@ -84,6 +84,12 @@ CONFIGS: Dict[int, Config] = {
               **_LLAMA),
     5: Config("cfg5-llama8b-128k", n_chunks=256, n_query=256, seed=5,
               n_relevant=1311, **_LLAMA),
+    # layer geometry of the 14B Qwen models the paper also evaluates (Sec. 5.1): 40 query
+    # heads over 8 kv heads (groups of 5), hidden 5120 - public model configurations
+    6: Config("cfg6-qwen14b-4k", "bf16", 8, 512, 64, 40, 8, 128, 5120, 1000000.0,
+              seed=6, n_relevant=41),
+    7: Config("cfg7-qwen14b-32k", "bf16", 64, 512, 128, 40, 8, 128, 5120, 1000000.0,
+              seed=7, n_relevant=328, n_salient=655),
 }
 
 

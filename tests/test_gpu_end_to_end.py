@@ -58,7 +58,7 @@ def check_layer(cfg, sr, dev_layer, want, sample_rows=None):
     return kc, vc
 
 
-@pytest.mark.parametrize("cid", [1, 2])
+@pytest.mark.parametrize("cid", [1, 2, 6])
 def test_whole_path_matches_oracle(gpu_device, cid):
     cfg = synth.CONFIGS[cid]
     layers, info = workload.build(cfg)
