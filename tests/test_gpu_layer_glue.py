@@ -170,3 +170,44 @@ def test_glue_rejects_bad_arguments(gpu_device):
     assert lib.pkv_linear_rows(1, None, None, None, None, 0, 16, 8, None, 0, st) == 0
     assert lib.pkv_rmsnorm_rows(1, None, None, None, 1e-5, None, 0, 16, st) == 0
     torch.cuda.synchronize()
+
+
+def test_glue_at_the_benchmark_widths_on_sampled_rows(gpu_device):
+    """The launch configuration bench.py times (6681 rows, hidden 4096, MLP 14336: 12 rounds of
+    256 x 256 tiles with a ragged last row tile), checked on a seeded sample of rows that the
+    oracle computes one by one; plus the 128-row launches of the scoring stage, whose
+    contraction is split."""
+    dtype, hid, inter = "bf16", 4096, 14336
+    g = np.random.default_rng(91)
+    wo = rnd(92, (hid, hid), dtype, 1.0 / np.sqrt(hid))
+    wg = rnd(93, (inter, hid), dtype, 2.0 / np.sqrt(hid))
+    wu = rnd(94, (inter, hid), dtype, 1.0 / np.sqrt(hid))
+    wd = rnd(95, (hid, inter), dtype, 1.0 / np.sqrt(inter))
+    gain = rnd(96, (hid,), dtype, 0.1, ) + 1.0
+    gain = synth.to_storage(gain, dtype)
+    d_wo, d_wg, d_wu, d_wd, d_gain = (dev(t, dtype, gpu_device) for t in (wo, wg, wu, wd, gain))
+    for m in (6681, 128):
+        x = rnd(97, (m, hid), dtype)
+        res = rnd(98, (m, hid), dtype, 2.0)
+        act = rnd(99, (m, inter), dtype, 0.5)
+        pick = np.unique(np.concatenate([[0, m - 1, min(m - 1, 255), min(m - 1, 256)],
+                                         g.choice(m, 12, replace=False)]))
+        d_x, d_res, d_act = (dev(t, dtype, gpu_device) for t in (x, res, act))
+        ws = torch.empty(max(api.pkv_glue_workspace_bytes(TDT[dtype], m, hid, inter),
+                             api.pkv_glue_workspace_bytes(TDT[dtype], m, inter, hid),
+                             api.pkv_glue_workspace_bytes(TDT[dtype], m, hid, hid), 256),
+                         dtype=torch.uint8, device=gpu_device)
+        y = torch.empty((m, hid), dtype=TDT[dtype], device=gpu_device)
+        api.pkv_rmsnorm_rows(d_res, None, d_gain, 1e-5, y)
+        assert rel_err(host(y)[pick], MO.rmsnorm_rows(res[pick], None, gain, 1e-5, dtype)) <= TOL[dtype]
+        api.pkv_linear_rows(d_x, d_wo, d_res, y, ws)
+        assert rel_err(host(y)[pick], MO.linear_rows(x[pick], wo, res[pick], dtype)) <= TOL[dtype]
+        gbuf = torch.empty((m, inter), dtype=TDT[dtype], device=gpu_device)
+        api.pkv_swiglu_rows(d_x, d_wg, d_wu, gbuf, ws)
+        got = host(gbuf)
+        assert np.isfinite(got).all()
+        assert rel_err(got[pick], MO.swiglu_up(x[pick], wg, wu, dtype)) <= TOL[dtype]
+        api.pkv_linear_rows(d_act, d_wd, d_res, y, ws)
+        got = host(y)
+        assert np.isfinite(got).all()
+        assert rel_err(got[pick], MO.linear_rows(act[pick], wd, res[pick], dtype)) <= TOL[dtype]
