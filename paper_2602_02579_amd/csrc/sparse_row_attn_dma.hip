@@ -57,6 +57,15 @@ __device__ __forceinline__ void wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// O^T += V^T P^T with the accumulator tile pinned to the accumulation registers: the
+// output accumulators are never touched by the VALU inside the loop, so they do not
+// compete with the score tiles (which the softmax reads) for the ordinary registers.
+// The compiler does not see through the statement: every operand it reads was written
+// several instructions earlier, and the same accumulator recurs only every eighth MFMA.
+__device__ __forceinline__ void mfma32_acc(bf16x8 a, bf16x8 b, f32x16& c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
 __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_red[kAttnThreads / 64];
@@ -328,7 +337,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         PKV_LOAD_KA(KST, KH)                                                             \
         _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                               \
             const int kk_ = i_ >> 2, db_ = i_ & 3;                                       \
-            o_acc[db_][0] = mfma32(va[kk_][db_], pb[kk_][0], o_acc[db_][0]);             \
+            mfma32_acc(va[kk_][db_], pb[kk_][0], o_acc[db_][0]);                         \
             if (i_ < 7) { PKV_SM_STEP(1, 8 + i_, CUR, 1, 9 + i_, T0, MASK) }             \
             else { PKV_SM_STEP(1, 15, NXT, 0, 0, (T0) + 32, MASK) }                      \
             __builtin_amdgcn_sched_barrier(0);                                           \
@@ -337,7 +346,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         __builtin_amdgcn_sched_barrier(0);                                               \
         _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) {                               \
             const int kk_ = i_ >> 2, db_ = i_ & 3;                                       \
-            o_acc[db_][1] = mfma32(va[kk_][db_], pb[kk_][1], o_acc[db_][1]);             \
+            mfma32_acc(va[kk_][db_], pb[kk_][1], o_acc[db_][1]);                         \
             PKV_SM_STEP(0, i_, NXT, 0, 1 + i_, (T0) + 32, MASK)                          \
             __builtin_amdgcn_sched_barrier(0);                                           \
         }                                                                                \
@@ -409,6 +418,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         PKV_TILE(j, (j + 1) & 3, j & 3, (j + 3) & 3, (j + 2) & 3, true)
     }
     wait_vm<0>();   // nothing may still be writing LDS when the workgroup retires
+    // the last O^T MFMAs were issued behind the compiler's back: let them retire before
+    // the accumulators are read
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
 #undef PKV_DMA_K
 #undef PKV_DMA_V
