@@ -117,8 +117,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         if (tid == 0) p.flags[tile * p.hkv + g] = 0;
         return;
     }
-    // sub-steps [0, u_unm) lie entirely at or below every limit of this wave
-    const int u_unm = __builtin_amdgcn_readfirstlane(lmin == 0x7fffffff ? 0 : (lmin + 1) / 32);
+    // sub-steps [0, u_unm) lie entirely at or below every limit of this wave.  A wave
+    // without any valid column (the ragged last row tile) has nothing to mask: whatever
+    // it computes is dropped, so it takes the cheaper unmasked path throughout.
+    const int u_unm = __builtin_amdgcn_readfirstlane(lmin == 0x7fffffff ? 0x3fffffff
+                                                                        : (lmin + 1) / 32);
 
     // ---- Q as B operands -----------------------------------------------------------
     bf16x8 qreg[2][KC];
