@@ -202,22 +202,30 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     // The eight fill instructions of a tile (K tile J+3, V^T tile J+2) go out in four
     // pairs spread over the tile's four scheduling regions: a burst of eight from each
     // of the four waves fills the memory pipeline's queue and stalls the waves.
+    // Only the last tile of the cache can be ragged (rows past the cache re-read its last
+    // row): its clamped offsets are formed once, every other tile uses the plain ones.
     const bf16_t* gbk_;
     const bf16_t* gbv_;
-    uint32_t kofs_[4];
+    bool k_full_;
+    uint32_t kofs_last[4];
+    {
+        const int last_ = (p.n_keys - 1) % kBN;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            kofs_last[i] = (uint32_t)min(krow[i], last_) * k_row_bytes + kchunk16[i];
+    }
 #define PKV_DMA_PREP(J)                                                                  \
     {                                                                                    \
         const int tk_ = min((J) + 3, n_iter - 1);                                        \
         const int t0k_ = tk_ * kBN;                                                      \
         gbk_ = k_head + (int64_t)t0k_ * p.hkv * D;                                       \
-        const int last_ = p.n_keys - 1 - t0k_;  /* rows past the cache re-read its last */ \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                    \
-            kofs_[i] = (uint32_t)min(krow[i], last_) * k_row_bytes + kchunk16[i];        \
+        k_full_ = t0k_ + kBN <= p.n_keys;   /* wave-uniform */                           \
         gbv_ = v_head + min((J) + 2, n_iter - 1) * kBN;                                  \
     }
 #define PKV_DMA_PAIR(I, SDK, SDV)                                                        \
     {                                                                                    \
-        dma16(gbk_, kofs_[I], lds_k_wave + (SDK) * kStageK + (I) * 1024);                \
+        dma16(gbk_, k_full_ ? voff_k[I] : kofs_last[I],                                  \
+              lds_k_wave + (SDK) * kStageK + (I) * 1024);                                \
         dma16(gbv_, voff_v[I], lds_v_wave + (SDV) * kStageV + (I) * 1024);               \
     }
 
