@@ -62,7 +62,11 @@ __device__ __forceinline__ void wait_vm() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-__device__ __forceinline__ float silu_f32(float a) { return a / (1.f + __expf(-a)); }
+// silu(a) = a / (1 + e^-a) with the hardware reciprocal (1 ulp): the result is rounded to
+// bf16 right away, and a full-precision division would cost ten instructions per element
+__device__ __forceinline__ float silu_f32(float a) {
+    return a * __builtin_amdgcn_rcpf(1.f + __expf(-a));
+}
 
 // EXTRA (Q | K | V mode only): the launch has projection biases and/or per-head norm gains
 template <int MODE, bool EXTRA = false>
