@@ -404,6 +404,17 @@ def main():
                      "flops_per_launch": flops, "avg_launch_s": t_attn},
         "breakdown": breakdown,
     }
+    # the same pass with steps 4a + 4b fused into one call (outside `value`)
+    sr_f = pipeline.SelectiveRecompute(cfg, device, fused_scatter=True)
+    sr_f.run(layers)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sr_f.run(layers)
+    torch.cuda.synchronize()
+    result["ms_per_step_fused_cache_update"] = round(
+        (time.perf_counter() - t0) / args.steps * 1e3, 4)
+    del sr_f
     if args.model_layers > 0 and cfg.dtype == "bf16":
         del layers, sr
         torch.cuda.empty_cache()

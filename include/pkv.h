@@ -201,6 +201,25 @@ pkv_status pkv_gather_qkv_proj_ex(const pkv_layer_cfg* cfg,
                                   void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Steps 4a + 4b in one call (Algorithm 1: the recomputed K/V of the selected and
+ * the query rows replace the cache rows): as pkv_gather_qkv_proj_ex, but K and V of
+ * output row i are written straight to row dst_row[i] of k_cache / v_cache
+ * ([n_cache, Hkv, D]) instead of to separate [m, Hkv, D] buffers followed by
+ * pkv_scatter_kv.  q_out ([m, Hq, D], may be NULL) is written as before.  dst_row
+ * values must be distinct and lie in [0, n_cache) (device data, not checked);
+ * the caches must not overlap hidden or the weights.  variant may be NULL.
+ */
+pkv_status pkv_gather_qkv_proj_scatter(const pkv_layer_cfg* cfg,
+                                       const void* hidden, const int32_t* row_idx,
+                                       const int32_t* row_pos, const void* wq,
+                                       const void* wk, const void* wv,
+                                       const pkv_proj_variant* variant,
+                                       void* q_out, void* k_cache, void* v_cache,
+                                       const int32_t* dst_row, int64_t m,
+                                       int64_t n_cache, void* ws, size_t ws_bytes,
+                                       void* stream);
+
+/*
  * Step 4b - cache update (paper: Algorithm 1 "Update layer-wise KV cache":
  * rows in T_p take the recomputed K/V, all other rows are reused as they
  * are; the user-query K/V are appended after the context).

@@ -18,7 +18,8 @@ import torch
 
 __all__ = ["LayerCfg", "PkvError", "load_library", "library_path",
            "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
-           "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_scatter_kv",
+           "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex",
+           "pkv_gather_qkv_proj_scatter", "pkv_scatter_kv",
            "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
            "pkv_glue_workspace_bytes",
            "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
@@ -30,8 +31,8 @@ CALL_GATHER_QKV_PROJ, CALL_SCATTER_KV, CALL_SPARSE_ROW_ATTN = 4, 5, 6
 
 EXPORTED_SYMBOLS = [
     "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
-    "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_scatter_kv", "pkv_sparse_row_attn",
-    "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
+    "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_gather_qkv_proj_scatter",
+    "pkv_scatter_kv", "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
     "pkv_glue_workspace_bytes",
     "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
 ]
@@ -108,6 +109,9 @@ def load_library() -> ctypes.CDLL:
     lib.pkv_gather_qkv_proj_ex.argtypes = [cfgp, vp, i32p, i32p, vp, vp, vp,
                                            ctypes.POINTER(_CVariant), vp, vp, vp,
                                            i64, vp, ctypes.c_size_t, vp]
+    lib.pkv_gather_qkv_proj_scatter.argtypes = [cfgp, vp, i32p, i32p, vp, vp, vp,
+                                                ctypes.POINTER(_CVariant), vp, vp, vp, i32p,
+                                                i64, i64, vp, ctypes.c_size_t, vp]
     lib.pkv_scatter_kv.argtypes = [cfgp, vp, vp, i32p, vp, vp, i64, i64, vp]
     lib.pkv_sparse_row_attn.argtypes = [cfgp, vp, vp, vp, i32p, vp, f32p, i64, i64,
                                         ctypes.c_float, vp, ctypes.c_size_t, vp]
@@ -121,7 +125,8 @@ def load_library() -> ctypes.CDLL:
     lib.pkv_glue_workspace_bytes.argtypes = [i32, i64, i64, i64]
     lib.pkv_glue_workspace_bytes.restype = ctypes.c_size_t
     for name in ("pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
-                 "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_scatter_kv",
+                 "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex",
+                 "pkv_gather_qkv_proj_scatter", "pkv_scatter_kv",
                  "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows",
                  "pkv_swiglu_rows"):
         getattr(lib, name).restype = ctypes.c_int
@@ -292,6 +297,42 @@ def pkv_gather_qkv_proj_ex(cfg: LayerCfg, hidden: torch.Tensor,
         _ptr(row_pos, torch.int32, "row_pos"), _ptr(wq, dt, "wq"), _ptr(wk, dt, "wk"),
         _ptr(wv, dt, "wv"), ctypes.byref(var), _ptr(q_out, dt, "q_out"),
         _ptr(k_out, dt, "k_out"), _ptr(v_out, dt, "v_out"), m, wp, wb, _stream()))
+
+
+def pkv_gather_qkv_proj_scatter(cfg: LayerCfg, hidden: torch.Tensor,
+                                row_idx: Optional[torch.Tensor], row_pos: torch.Tensor,
+                                wq: Optional[torch.Tensor], wk: torch.Tensor, wv: torch.Tensor,
+                                q_out: Optional[torch.Tensor], k_cache: torch.Tensor,
+                                v_cache: torch.Tensor, dst_row: torch.Tensor,
+                                ws: Optional[torch.Tensor] = None, *,
+                                bq: Optional[torch.Tensor] = None,
+                                bk: Optional[torch.Tensor] = None,
+                                bv: Optional[torch.Tensor] = None,
+                                q_norm: Optional[torch.Tensor] = None,
+                                k_norm: Optional[torch.Tensor] = None,
+                                norm_eps: float = 1e-6) -> None:
+    m = _check_proj_args(cfg, hidden, row_idx, row_pos, wq, wk, wv, q_out, None, None)
+    dt = cfg.torch_dtype
+    n_cache = k_cache.shape[0]
+    if tuple(k_cache.shape) != (n_cache, cfg.n_kv_heads, cfg.head_dim) or \
+            v_cache.shape != k_cache.shape:
+        raise ValueError("caches must be [n_cache, Hkv, D]")
+    if tuple(dst_row.shape) != (m,):
+        raise ValueError("dst_row must be [m]")
+
+    def raw(t, name):
+        p = _ptr(t, dt, name)
+        return None if p is None else p.value
+    var = _CVariant(raw(bq, "bq"), raw(bk, "bk"), raw(bv, "bv"), raw(q_norm, "q_norm"),
+                    raw(k_norm, "k_norm"), float(norm_eps))
+    wp, wb = _ws(ws)
+    c = cfg._c()
+    _check("pkv_gather_qkv_proj_scatter", load_library().pkv_gather_qkv_proj_scatter(
+        ctypes.byref(c), _ptr(hidden, dt, "hidden"), _ptr(row_idx, torch.int32, "row_idx"),
+        _ptr(row_pos, torch.int32, "row_pos"), _ptr(wq, dt, "wq"), _ptr(wk, dt, "wk"),
+        _ptr(wv, dt, "wv"), ctypes.byref(var), _ptr(q_out, dt, "q_out"),
+        _ptr(k_cache, dt, "k_cache"), _ptr(v_cache, dt, "v_cache"),
+        _ptr(dst_row, torch.int32, "dst_row"), m, n_cache, wp, wb, _stream()))
 
 
 def pkv_scatter_kv(cfg: LayerCfg, k_new: torch.Tensor, v_new: torch.Tensor,

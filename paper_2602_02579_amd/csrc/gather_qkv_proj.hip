@@ -27,6 +27,7 @@ struct ProjExtra {
     const void* bias[3];
     const void* gain[2];
     float eps;
+    const int32_t* dst_row;   // fused cache update of K and V (null = plain outputs)
 };
 
 template <typename T>
@@ -115,7 +116,8 @@ __global__ __launch_bounds__(256) void qkv_proj_generic(
             ra = a * cs - b * sn;
             rb = b * cs + a * sn;
         }
-        T* o = out + ((int64_t)r * heads_out + head_local) * d;
+        const int64_t orow = (mat != 0 && ex.dst_row) ? ex.dst_row[r] : r;
+        T* o = out + (orow * heads_out + head_local) * d;
         o[i] = Elem<T>::from_f32(ra);
         o[i + half] = Elem<T>::from_f32(rb);
     }
@@ -268,7 +270,8 @@ __global__ __launch_bounds__(256, 2) void qkv_proj_mfma(ProjParams p) {
                 a = ra;
                 b = rb;
             }
-            bf16_t* o = out + ((int64_t)row * heads_out + head) * D + i;
+            const int64_t orow = (mat != 0 && p.dst_row) ? p.dst_row[row] : row;
+            bf16_t* o = out + (orow * heads_out + head) * D + i;
             o[0] = (bf16_t)a;
             o[HALF] = (bf16_t)b;
         }
@@ -293,10 +296,12 @@ size_t gather_qkv_proj_ws_bytes(const pkv_layer_cfg& cfg, int64_t m) {
 pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
                                   const int32_t* row_idx, const int32_t* row_pos,
                                   const void* wq, const void* wk, const void* wv,
-                                  const pkv_proj_variant* var, void* q_out, void* k_out,
-                                  void* v_out, int64_t m, void* ws, hipStream_t st) {
+                                  const pkv_proj_variant* var, const int32_t* dst_row,
+                                  void* q_out, void* k_out, void* v_out, int64_t m, void* ws,
+                                  hipStream_t st) {
     if (m == 0) return PKV_OK;
     ProjExtra ex = {};
+    ex.dst_row = dst_row;
     if (var) {
         ex.bias[0] = var->bq; ex.bias[1] = var->bk; ex.bias[2] = var->bv;
         ex.gain[0] = var->q_norm; ex.gain[1] = var->k_norm;
@@ -324,6 +329,7 @@ pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
         for (int i = 0; i < 3; ++i) p.bias[i] = (const bf16_t*)ex.bias[i];
         for (int i = 0; i < 2; ++i) p.norm_w[i] = (const bf16_t*)ex.gain[i];
         p.norm_eps = ex.eps;
+        p.dst_row = dst_row;
         if (proj_dma128_supported(cfg, m)) {
             const int tq = q_out ? hq * d / kProjDmaTile : 0;
             const int tkv = k_out ? hkv * d / kProjDmaTile : 0;

@@ -68,7 +68,8 @@ __device__ __forceinline__ float silu_f32(float a) {
     return a * __builtin_amdgcn_rcpf(1.f + __expf(-a));
 }
 
-// EXTRA (Q | K | V mode only): the launch has projection biases and/or per-head norm gains
+// EXTRA (Q | K | V mode only): the launch has projection biases, per-head norm gains and/or
+// a fused cache update (K/V rows stored at dst_row)
 template <int MODE, bool EXTRA = false>
 __global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_tiles,
                                                        int n_tiles, int per_xcd) {
@@ -415,8 +416,10 @@ __global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_t
             const int tok = idx >> 4, ch = idx & 15;
             const int row = row0 + wt * 128 + half * 64 + tok;
             const uint4 v = *reinterpret_cast<const uint4*>(epi + tok * kEpiStride + ch * 16);
-            if (row < p.m)
-                *reinterpret_cast<uint4*>(out + ((int64_t)row * heads_out + head) * D + ch * 8) = v;
+            if (row < p.m) {
+                const int64_t orow = (EXTRA && mat != 0 && p.dst_row) ? p.dst_row[row] : row;
+                *reinterpret_cast<uint4*>(out + (orow * heads_out + head) * D + ch * 8) = v;
+            }
         }
     }
 }
@@ -465,7 +468,8 @@ __global__ __launch_bounds__(256) void proj_splitk_finish_kernel(ProjParams p) {
         a = ra;
         b = rb;
     }
-    bf16_t* o = out + ((int64_t)row * heads_out + head) * D + i;
+    const int64_t orow = (mat != 0 && p.dst_row) ? p.dst_row[row] : row;
+    bf16_t* o = out + (orow * heads_out + head) * D + i;
     o[0] = (bf16_t)a;
     o[D / 2] = (bf16_t)b;
 }
@@ -571,7 +575,8 @@ pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
 }  // namespace
 
 pkv_status launch_proj_dma128(const ProjParams& p, hipStream_t st) {
-    const bool extra = p.bias[0] || p.bias[1] || p.bias[2] || p.norm_w[0] || p.norm_w[1];
+    const bool extra = p.bias[0] || p.bias[1] || p.bias[2] || p.norm_w[0] || p.norm_w[1] ||
+                       p.dst_row;
     return extra ? launch_tiles<kProjRope, true>(p, st) : launch_tiles<kProjRope, false>(p, st);
 }
 

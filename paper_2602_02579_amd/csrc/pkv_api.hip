@@ -94,8 +94,34 @@ pkv_status pkv_gather_qkv_proj_ex(const pkv_layer_cfg* cfg, const void* hidden,
     if (k_out && (!wk || !wv)) return PKV_ERR_NULL;
     const size_t need = align256(gather_qkv_proj_ws_bytes(*cfg, m));
     if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
-    return launch_gather_qkv_proj(*cfg, hidden, row_idx, row_pos, wq, wk, wv, variant, q_out,
-                                  k_out, v_out, m, ws, (hipStream_t)stream);
+    return launch_gather_qkv_proj(*cfg, hidden, row_idx, row_pos, wq, wk, wv, variant, nullptr,
+                                  q_out, k_out, v_out, m, ws, (hipStream_t)stream);
+}
+
+pkv_status pkv_gather_qkv_proj_scatter(const pkv_layer_cfg* cfg, const void* hidden,
+                                       const int32_t* row_idx, const int32_t* row_pos,
+                                       const void* wq, const void* wk, const void* wv,
+                                       const pkv_proj_variant* variant, void* q_out,
+                                       void* k_cache, void* v_cache, const int32_t* dst_row,
+                                       int64_t m, int64_t n_cache, void* ws, size_t ws_bytes,
+                                       void* stream) {
+    pkv_status st = check_cfg(cfg);
+    if (st != PKV_OK) return st;
+    if (m < 0 || m > kMaxTokens || n_cache < 0 || n_cache > kMaxTokens || m > n_cache)
+        return PKV_ERR_SHAPE;
+    if (variant) {
+        if ((variant->q_norm == nullptr) != (variant->k_norm == nullptr)) return PKV_ERR_NULL;
+        if (variant->q_norm && (!(variant->norm_eps >= 0.f) || !std::isfinite(variant->norm_eps)))
+            return PKV_ERR_SHAPE;
+    }
+    if (m == 0) return PKV_OK;
+    if (!hidden || !row_pos || !wk || !wv || !k_cache || !v_cache || !dst_row)
+        return PKV_ERR_NULL;
+    if (q_out && !wq) return PKV_ERR_NULL;
+    const size_t need = align256(gather_qkv_proj_ws_bytes(*cfg, m));
+    if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
+    return launch_gather_qkv_proj(*cfg, hidden, row_idx, row_pos, wq, wk, wv, variant, dst_row,
+                                  q_out, k_cache, v_cache, m, ws, (hipStream_t)stream);
 }
 
 pkv_status pkv_gather_qkv_proj(const pkv_layer_cfg* cfg, const void* hidden,

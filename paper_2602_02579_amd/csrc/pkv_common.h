@@ -93,8 +93,9 @@ pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
 pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
                                   const int32_t* row_idx, const int32_t* row_pos,
                                   const void* wq, const void* wk, const void* wv,
-                                  const pkv_proj_variant* var, void* q_out, void* k_out,
-                                  void* v_out, int64_t m, void* ws, hipStream_t st);
+                                  const pkv_proj_variant* var, const int32_t* dst_row,
+                                  void* q_out, void* k_out, void* v_out, int64_t m, void* ws,
+                                  hipStream_t st);
 size_t gather_qkv_proj_ws_bytes(const pkv_layer_cfg& cfg, int64_t m);
 
 size_t sparse_row_attn_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m);

@@ -25,6 +25,9 @@ struct ProjParams {
     const bf16_t* bias[3];
     const bf16_t* norm_w[2];
     float norm_eps;
+    // fused cache update: K and V of output row i go to row dst_row[i] of out[1] / out[2]
+    // (the caches) instead of row i; null = plain outputs.  Q is never redirected.
+    const int32_t* dst_row;
 };
 
 // what the tile's epilogue does with the accumulators

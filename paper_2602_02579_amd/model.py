@@ -66,8 +66,6 @@ class CarriedRows:
         self.h = new(rows_max, hid)                     # carried hidden states
         self.x = new(rows_max, hid)                     # normalised rows
         self.q = new(rows_max, hq, d)
-        self.k_new = new(rows_max, hkv, d)
-        self.v_new = new(rows_max, hkv, d)
         self.attn = new(rows_max, hq, d)
         self.g = new(rows_max, self.inter)
         tdt = dt
@@ -88,20 +86,19 @@ class CarriedRows:
                score: Optional[bool]) -> None:
         lc, ws = self.lc, self.ws
         h, x = self.h[:cnt], self.x[:cnt]
-        q, k_new, v_new = self.q[:cnt], self.k_new[:cnt], self.v_new[:cnt]
+        q = self.q[:cnt]
         attn, g = self.attn[:cnt], self.g[:cnt]
         api.pkv_rmsnorm_rows(h, None, L["w_in"], self.eps, x)
-        if any(v in L for v in VARIANT_WEIGHTS):
-            api.pkv_gather_qkv_proj_ex(lc, x, None, rows, L["wq"], L["wk"], L["wv"], q, k_new,
-                                       v_new, ws=ws, norm_eps=self.eps,
-                                       **{v: L[v] for v in VARIANT_WEIGHTS if v in L})
-        else:
-            api.pkv_gather_qkv_proj(lc, x, None, rows, L["wq"], L["wk"], L["wv"], q, k_new,
-                                    v_new, ws=ws)
+        # Q/K/V of the rows; K and V go straight to their cache rows (steps 4a + 4b).  The
+        # score of Stage I reads only the context rows of the key cache, which the query
+        # rows' own keys (stored behind the context) do not touch.
+        api.pkv_gather_qkv_proj_scatter(lc, x, None, rows, L["wq"], L["wk"], L["wv"], q,
+                                        L["k_cache"], L["v_cache"], rows, ws=ws,
+                                        norm_eps=self.eps,
+                                        **{v: L[v] for v in VARIANT_WEIGHTS if v in L})
         if score is not None:
             api.pkv_query_score(lc, q, L["k_cache"][:self.n], self.score, accumulate=score,
                                 ws=ws)
-        api.pkv_scatter_kv(lc, k_new, v_new, rows, L["k_cache"], L["v_cache"])
         api.pkv_sparse_row_attn(lc, q, L["k_cache"], L["v_cache"], rows, attn, None, ws=ws)
         api.pkv_linear_rows(attn.view(cnt, -1), L["wo"], h, h, ws=ws)
         api.pkv_rmsnorm_rows(h, None, L["w_post"], self.eps, x)

@@ -42,8 +42,11 @@ def upload_layer(cfg: Config, layer: Dict[str, np.ndarray],
 class SelectiveRecompute:
     """Work buffers and the per-layer call sequence for one configuration."""
 
-    def __init__(self, cfg: Config, device: torch.device, k: Optional[int] = None):
+    def __init__(self, cfg: Config, device: torch.device, k: Optional[int] = None,
+                 fused_scatter: bool = False):
         self.cfg = cfg
+        # True: steps 4a and 4b in one call (K/V go straight to their cache rows)
+        self.fused_scatter = fused_scatter
         self.lc = layer_cfg(cfg)
         self.device = device
         n, qn = cfg.n_ctx, cfg.n_query
@@ -87,10 +90,16 @@ class SelectiveRecompute:
 
     # ---- Stage II --------------------------------------------------------
     def recompute_layer(self, L: Dict[str, torch.Tensor]) -> None:
-        api.pkv_gather_qkv_proj(self.lc, L["hidden"], self.rows, self.rows, L["wq"],
-                                L["wk"], L["wv"], self.q, self.k_new, self.v_new, ws=self.ws)
-        api.pkv_scatter_kv(self.lc, self.k_new, self.v_new, self.rows, L["k_cache"],
-                           L["v_cache"])
+        if self.fused_scatter:
+            api.pkv_gather_qkv_proj_scatter(self.lc, L["hidden"], self.rows, self.rows, L["wq"],
+                                            L["wk"], L["wv"], self.q, L["k_cache"],
+                                            L["v_cache"], self.rows, ws=self.ws)
+        else:
+            api.pkv_gather_qkv_proj(self.lc, L["hidden"], self.rows, self.rows, L["wq"],
+                                    L["wk"], L["wv"], self.q, self.k_new, self.v_new,
+                                    ws=self.ws)
+            api.pkv_scatter_kv(self.lc, self.k_new, self.v_new, self.rows, L["k_cache"],
+                               L["v_cache"])
         api.pkv_sparse_row_attn(self.lc, self.q, L["k_cache"], L["v_cache"], self.rows,
                                 self.out, self.lse, ws=self.ws)
 

@@ -150,3 +150,49 @@ def test_model_with_block_variant_matches_oracle(gpu_device, case, variant):
         assert rel_err(host(L["k_cache"])[rows], want["k_cache"][li][rows]) <= tol
         assert rel_err(host(L["v_cache"])[rows], want["v_cache"][li][rows]) <= tol
     assert rel_err(host(h_final), want["h_final"]) <= tol
+
+
+@pytest.mark.parametrize("dtype,m,hq,hkv,d,hid,n_rows", SHAPES + [("bf16", 200, 4, 2, 64, 128, 300)])
+@pytest.mark.parametrize("with_q", [True, False])
+def test_fused_projection_and_cache_update(gpu_device, dtype, m, hq, hkv, d, hid, n_rows, with_q):
+    """pkv_gather_qkv_proj_scatter against the oracle's projection followed by its cache
+    update, and bit for bit against the two separate GPU calls."""
+    cfg = api.LayerCfg(hq, hkv, d, hid, 500000.0, dtype)
+    g = np.random.default_rng(75)
+    n_cache = n_rows + 37
+    hidden = rnd(76, (n_rows, hid), dtype)
+    w = [rnd(77 + i, (h * d, hid), dtype, 1.0 / np.sqrt(hid)) for i, h in enumerate((hq, hkv, hkv))]
+    rows = np.sort(g.choice(n_rows, m, replace=False)).astype(np.int32) if n_rows > m else \
+        np.arange(m, dtype=np.int32)
+    dst = g.permutation(n_cache)[:m].astype(np.int32)          # distinct, unsorted targets
+    kc0 = rnd(80, (n_cache, hkv, d), dtype)
+    vc0 = rnd(81, (n_cache, hkv, d), dtype)
+    q_w, k_w, v_w = O.project_qkv_rows(hidden, rows, dst, *w, hq, hkv, d, cfg.rope_theta, dtype)
+    kc_w, vc_w = O.scatter_kv(kc0.astype(np.float64), vc0.astype(np.float64), k_w, v_w, dst)
+
+    d_hidden = dev(hidden, dtype, gpu_device)
+    d_w = [dev(x, dtype, gpu_device) for x in w]
+    d_rows = torch.from_numpy(rows).to(gpu_device)
+    d_dst = torch.from_numpy(dst).to(gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, cfg, 0, m), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    kc, vc = dev(kc0, dtype, gpu_device), dev(vc0, dtype, gpu_device)
+    q = torch.full((m, hq, d), float("nan"), dtype=TDT[dtype], device=gpu_device) if with_q else None
+    api.pkv_gather_qkv_proj_scatter(cfg, d_hidden, d_rows, d_dst, d_w[0] if with_q else None,
+                                    d_w[1], d_w[2], q, kc, vc, d_dst, ws=ws)
+    # the two-call path on the same inputs
+    kc2, vc2 = dev(kc0, dtype, gpu_device), dev(vc0, dtype, gpu_device)
+    q2 = torch.empty((m, hq, d), dtype=TDT[dtype], device=gpu_device)
+    k_new = torch.empty((m, hkv, d), dtype=TDT[dtype], device=gpu_device)
+    v_new = torch.empty_like(k_new)
+    api.pkv_gather_qkv_proj(cfg, d_hidden, d_rows, d_dst, *d_w, q2, k_new, v_new, ws=ws)
+    api.pkv_scatter_kv(cfg, k_new, v_new, d_dst, kc2, vc2)
+    assert torch.equal(kc, kc2) and torch.equal(vc, vc2)
+    if with_q:
+        assert torch.equal(q, q2)
+        assert rel_err(host(q), q_w) <= TOL[dtype]
+    assert rel_err(host(kc), kc_w) <= TOL[dtype]
+    assert rel_err(host(vc), vc_w) <= TOL[dtype]
+    rest = np.setdiff1d(np.arange(n_cache), dst)
+    assert np.array_equal(host(kc)[rest], kc0[rest].astype(np.float64))
+    assert np.array_equal(host(vc)[rest], vc0[rest].astype(np.float64))

@@ -34,9 +34,9 @@ def as64(layer):
     return {k: v.astype(np.float64) for k, v in layer.items()}
 
 
-def run_gpu(cfg, layers, device, k=None):
+def run_gpu(cfg, layers, device, k=None, fused_scatter=False):
     dev_layers = [pipeline.upload_layer(cfg, l, device) for l in layers]
-    sr = pipeline.SelectiveRecompute(cfg, device, k=k)
+    sr = pipeline.SelectiveRecompute(cfg, device, k=k, fused_scatter=fused_scatter)
     sr.run(dev_layers)
     torch.cuda.synchronize()
     return sr, dev_layers
@@ -76,6 +76,18 @@ def test_whole_path_matches_oracle(gpu_device, cid):
     assert rel_err(host(sr.q), want["q"]) <= TOL[cfg.dtype]
     assert rel_err(host(sr.out), want["out"]) <= TOL[cfg.dtype]
     assert np.abs(host(sr.lse) - want["lse"]).max() <= (2e-2 if cfg.dtype == "bf16" else 1e-3)
+
+
+def test_fused_cache_update_gives_the_same_bits(gpu_device):
+    """Steps 4a + 4b in one call (pkv_gather_qkv_proj_scatter) against the two-call path."""
+    cfg = synth.CONFIGS[2]
+    layers, _ = workload.build(cfg)
+    a, la = run_gpu(cfg, layers, gpu_device)
+    b, lb = run_gpu(cfg, layers, gpu_device, fused_scatter=True)
+    assert torch.equal(a.rows, b.rows)
+    assert torch.equal(la[0]["k_cache"], lb[0]["k_cache"])
+    assert torch.equal(la[0]["v_cache"], lb[0]["v_cache"])
+    assert torch.equal(a.out, b.out) and torch.equal(a.q, b.q)
 
 
 def test_ratio_endpoints_on_gpu(gpu_device):
