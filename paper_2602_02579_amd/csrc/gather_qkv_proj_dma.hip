@@ -70,156 +70,24 @@ __device__ __forceinline__ float silu_f32(float a) {
 
 // EXTRA (Q | K | V mode only): the launch has projection biases, per-head norm gains and/or
 // a fused cache update (K/V rows stored at dst_row)
-template <int MODE, bool EXTRA = false>
-__global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_tiles,
-                                                       int n_tiles, int per_xcd) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int hh = lane >> 5, l32 = lane & 31;
-    const int wt = wave >> 1, wf = wave & 1;
+// what a tile is and which part of it a lane owns (filled by the kernels, read by the
+// epilogue)
+struct TileCtx {
+    int lane, wave, hh, l32, wt, wf;
+    int split, ft, mat, feat0, row0, heads_out;
+    bf16_t* out;
+};
 
-    // ---- which tile --------------------------------------------------------------
-    int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (logical >= n_tiles * p.n_ksplit) return;
-    const int split = logical / n_tiles;
-    logical -= split * n_tiles;
-    const int n_feat_tiles = p.tile_begin[3];
-    const int per_group = kGroup * n_feat_tiles;
-    const int group = logical / per_group;
-    const int first_tok = group * kGroup;
-    const int rows_in_group = min(kGroup, n_tok_tiles - first_tok);
-    const int within = logical - group * per_group;
-    const int tok_tile = first_tok + within % rows_in_group;
-    const int ft = within / rows_in_group;
-    int mat = 0;
-    if (MODE == kProjRope) {
-        if (ft >= p.tile_begin[1]) mat = 1;
-        if (ft >= p.tile_begin[2]) mat = 2;
-    }
-    const int feat0 = (ft - p.tile_begin[mat]) * T;   // first output feature of the tile
-    const bf16_t* w = p.w[mat];
-    bf16_t* out = p.out[mat];
-    const int heads_out = mat == 0 ? p.hq : p.hkv;
-    const int row0 = tok_tile * T;
-
-    const int n_k = p.hid / BK / p.n_ksplit;   // stages of this split; >= NS (launcher)
-    const int k_begin = split * n_k * BK;
-
-    // ---- fill side: wave w, instruction j covers rows 16 (4w + j) .. + 16 ------------
-    const int sw = (lane & 3) ^ ((lane >> 4) & 3);   // global chunk that lands at lane & 3
-    const bf16_t* xptr[4];
-    const bf16_t* wptr[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int r = (wave * 4 + j) * 16 + (lane >> 2);
-        const int gr = min(row0 + r, p.m - 1);
-        const int64_t src_row = p.row_idx ? p.row_idx[gr] : gr;
-        xptr[j] = p.hidden + src_row * p.hid + k_begin + sw * 8;
-        if (MODE == kProjGated) {
-            // tile row r: half r / 128 of the tile's 128 outputs, then 64 gate rows and
-            // 64 up rows, so that accumulator blocks (0, 1) and (2, 3) of a wave hold
-            // gate and up of the same outputs
-            const int f = ft * 128 + (r >> 7) * 64 + (r & 63);
-            wptr[j] = p.w[(r >> 6) & 1] + (int64_t)f * p.hid + k_begin + sw * 8;
-        } else {
-            wptr[j] = w + (int64_t)(feat0 + r) * p.hid + k_begin + sw * 8;
-        }
-    }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(lds0 + wave * 4 * 1024);
-    // one fill instruction: 16 rows of the token operand (which = 0) or of the
-    // feature operand (which = 1).  adv is BK, or 0 once the last stage has been
-    // requested: the ring then keeps re-reading that stage into slots nobody reads
-    // any more, which keeps the loop and its wait counts uniform.
-    auto issue_one = [&](int stage, int j, int which, int adv) {
-        const uint32_t base = lds_fill + stage * kStageBytes + j * 1024;
-        if (which == 0) {
-            dma16(xptr[j], base);
-            xptr[j] += adv;
-        } else {
-            dma16(wptr[j], base + kOperandBytes);
-            wptr[j] += adv;
-        }
-    };
-
-    // ---- read side -----------------------------------------------------------------
-    // operand of row r, sub-step ks: chunk ks*2 + hh at position chunk ^ ((r >> 2) & 3)
-    int off_x[2], off_w[2];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        const int pos = (ks * 2 + hh) ^ ((l32 >> 2) & 3);
-        off_x[ks] = (wt * 128 + l32) * kRowBytes + pos * 16;
-        off_w[ks] = kOperandBytes + (wf * 128 + l32) * kRowBytes + pos * 16;
-    }
-    bf16x8 fx[2][4], fw[2][4];
-    auto load_frags = [&](int stage, int ks, int slot) {
-        const unsigned char* sb = smem + stage * kStageBytes;
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            fw[slot][b] = *reinterpret_cast<const bf16x8*>(sb + off_w[ks] + b * 32 * kRowBytes);
-            fx[slot][b] = *reinterpret_cast<const bf16x8*>(sb + off_x[ks] + b * 32 * kRowBytes);
-        }
-    };
-
-    f32x16 acc[4][4];   // [feature block][token block]
-#pragma unroll
-    for (int fb = 0; fb < 4; ++fb)
-#pragma unroll
-        for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
-    // 16 MFMAs of one contraction sub-step.  One fill instruction goes out after every
-    // fourth MFMA (half a stage per sub-step), so the memory pipeline sees a steady
-    // trickle instead of a burst that stalls the wave; the operands of the next
-    // sub-step (stage lstage, sub-step lks) are read from LDS in the same rhythm,
-    // two per four MFMAs, into the other register slot
-    auto mfma16 = [&](int slot, int fill_stage, int j0, int adv, int lstage, int lks) {
-        const unsigned char* sb = smem + lstage * kStageBytes;
-#pragma unroll
-        for (int fb = 0; fb < 4; ++fb) {
-            fw[slot ^ 1][fb] = *reinterpret_cast<const bf16x8*>(sb + off_w[lks] + fb * 32 * kRowBytes);
-            fx[slot ^ 1][fb] = *reinterpret_cast<const bf16x8*>(sb + off_x[lks] + fb * 32 * kRowBytes);
-#pragma unroll
-            for (int tb = 0; tb < 4; ++tb)
-                acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[slot][fb], fx[slot][tb],
-                                                                      acc[fb][tb], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            issue_one(fill_stage, j0 + (fb >> 1), fb & 1, adv);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    // prologue: stages 0 .. NS-3 and the first half of stage NS-2 in flight
-#pragma unroll
-    for (int s = 0; s < NS - 2; ++s)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            issue_one(s, j, 0, BK);
-            issue_one(s, j, 1, BK);
-        }
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        issue_one(NS - 2, j, 0, BK);
-        issue_one(NS - 2, j, 1, BK);
-    }
-    wait_vm<8 * (NS - 3) + 4>();  // stage 0 of this wave has landed
-    __syncthreads();              // ... and everyone's
-    load_frags(0, 0, 0);
-    int st_cur = 0;               // t mod NS
-    for (int t = 0; t < n_k; ++t) {
-        const int st_next = st_cur + 1 == NS ? 0 : st_cur + 1;
-        const int st_fill = st_cur == 0 ? NS - 1 : st_cur - 1;          // (t + NS - 1) mod NS
-        const int st_fill_b = st_fill == 0 ? NS - 1 : st_fill - 1;      // (t + NS - 2) mod NS
-        mfma16(0, st_fill_b, 2, t + NS - 1 < n_k ? BK : 0, st_cur, 1);
-        wait_vm<8 * (NS - 3)>();  // stage t+1 has landed; the younger ones stay in flight
-        __syncthreads();          // ... for everyone; and everyone is done with stage t-1
-        mfma16(1, st_fill, 0, t + NS < n_k ? BK : 0, st_next, 0);
-        st_cur = st_next;
-    }
-    wait_vm<0>();                 // the ring's trailing fills must not land in the staging
-
+// rotate pairs in registers / add the residual / gate, round, stage through LDS, store
+// 16 B per lane; or store the fp32 partial tile of a split contraction.  Called after the
+// main loop, when nothing is still writing the LDS stages.
+template <int MODE, bool EXTRA>
+__device__ __forceinline__ void tile_epilogue(const ProjParams& p, f32x16 (&acc)[4][4],
+                                              const TileCtx& c, unsigned char* smem) {
+    const int lane = c.lane, wave = c.wave, hh = c.hh, l32 = c.l32, wt = c.wt, wf = c.wf;
+    const int split = c.split, ft = c.ft, mat = c.mat, feat0 = c.feat0, row0 = c.row0;
+    const int heads_out = c.heads_out;
+    bf16_t* out = c.out;
     // ---- epilogue: rotate pairs in registers, round once, stage, store 16 B per lane ----
     if (out == nullptr) return;   // uniform over the workgroup
     __syncthreads();              // LDS stages are free
@@ -424,6 +292,364 @@ __global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_t
     }
 }
 
+
+template <int MODE, bool EXTRA = false>
+__global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_tiles,
+                                                       int n_tiles, int per_xcd) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hh = lane >> 5, l32 = lane & 31;
+    const int wt = wave >> 1, wf = wave & 1;
+
+    // ---- which tile --------------------------------------------------------------
+    int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (logical >= n_tiles * p.n_ksplit) return;
+    const int split = logical / n_tiles;
+    logical -= split * n_tiles;
+    const int n_feat_tiles = p.tile_begin[3];
+    const int per_group = kGroup * n_feat_tiles;
+    const int group = logical / per_group;
+    const int first_tok = group * kGroup;
+    const int rows_in_group = min(kGroup, n_tok_tiles - first_tok);
+    const int within = logical - group * per_group;
+    const int tok_tile = first_tok + within % rows_in_group;
+    const int ft = within / rows_in_group;
+    int mat = 0;
+    if (MODE == kProjRope) {
+        if (ft >= p.tile_begin[1]) mat = 1;
+        if (ft >= p.tile_begin[2]) mat = 2;
+    }
+    const int feat0 = (ft - p.tile_begin[mat]) * T;   // first output feature of the tile
+    const bf16_t* w = p.w[mat];
+    bf16_t* out = p.out[mat];
+    const int heads_out = mat == 0 ? p.hq : p.hkv;
+    const int row0 = tok_tile * T;
+
+    const int n_k = p.hid / BK / p.n_ksplit;   // stages of this split; >= NS (launcher)
+    const int k_begin = split * n_k * BK;
+
+    // ---- fill side: wave w, instruction j covers rows 16 (4w + j) .. + 16 ------------
+    const int sw = (lane & 3) ^ ((lane >> 4) & 3);   // global chunk that lands at lane & 3
+    const bf16_t* xptr[4];
+    const bf16_t* wptr[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = (wave * 4 + j) * 16 + (lane >> 2);
+        const int gr = min(row0 + r, p.m - 1);
+        const int64_t src_row = p.row_idx ? p.row_idx[gr] : gr;
+        xptr[j] = p.hidden + src_row * p.hid + k_begin + sw * 8;
+        if (MODE == kProjGated) {
+            // tile row r: half r / 128 of the tile's 128 outputs, then 64 gate rows and
+            // 64 up rows, so that accumulator blocks (0, 1) and (2, 3) of a wave hold
+            // gate and up of the same outputs
+            const int f = ft * 128 + (r >> 7) * 64 + (r & 63);
+            wptr[j] = p.w[(r >> 6) & 1] + (int64_t)f * p.hid + k_begin + sw * 8;
+        } else {
+            wptr[j] = w + (int64_t)(feat0 + r) * p.hid + k_begin + sw * 8;
+        }
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(lds0 + wave * 4 * 1024);
+    // one fill instruction: 16 rows of the token operand (which = 0) or of the
+    // feature operand (which = 1).  adv is BK, or 0 once the last stage has been
+    // requested: the ring then keeps re-reading that stage into slots nobody reads
+    // any more, which keeps the loop and its wait counts uniform.
+    auto issue_one = [&](int stage, int j, int which, int adv) {
+        const uint32_t base = lds_fill + stage * kStageBytes + j * 1024;
+        if (which == 0) {
+            dma16(xptr[j], base);
+            xptr[j] += adv;
+        } else {
+            dma16(wptr[j], base + kOperandBytes);
+            wptr[j] += adv;
+        }
+    };
+
+    // ---- read side -----------------------------------------------------------------
+    // operand of row r, sub-step ks: chunk ks*2 + hh at position chunk ^ ((r >> 2) & 3)
+    int off_x[2], off_w[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int pos = (ks * 2 + hh) ^ ((l32 >> 2) & 3);
+        off_x[ks] = (wt * 128 + l32) * kRowBytes + pos * 16;
+        off_w[ks] = kOperandBytes + (wf * 128 + l32) * kRowBytes + pos * 16;
+    }
+    bf16x8 fx[2][4], fw[2][4];
+    auto load_frags = [&](int stage, int ks, int slot) {
+        const unsigned char* sb = smem + stage * kStageBytes;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            fw[slot][b] = *reinterpret_cast<const bf16x8*>(sb + off_w[ks] + b * 32 * kRowBytes);
+            fx[slot][b] = *reinterpret_cast<const bf16x8*>(sb + off_x[ks] + b * 32 * kRowBytes);
+        }
+    };
+
+    f32x16 acc[4][4];   // [feature block][token block]
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
+    // 16 MFMAs of one contraction sub-step.  One fill instruction goes out after every
+    // fourth MFMA (half a stage per sub-step), so the memory pipeline sees a steady
+    // trickle instead of a burst that stalls the wave; the operands of the next
+    // sub-step (stage lstage, sub-step lks) are read from LDS in the same rhythm,
+    // two per four MFMAs, into the other register slot
+    auto mfma16 = [&](int slot, int fill_stage, int j0, int adv, int lstage, int lks) {
+        const unsigned char* sb = smem + lstage * kStageBytes;
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) {
+            fw[slot ^ 1][fb] = *reinterpret_cast<const bf16x8*>(sb + off_w[lks] + fb * 32 * kRowBytes);
+            fx[slot ^ 1][fb] = *reinterpret_cast<const bf16x8*>(sb + off_x[lks] + fb * 32 * kRowBytes);
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb)
+                acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[slot][fb], fx[slot][tb],
+                                                                      acc[fb][tb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_one(fill_stage, j0 + (fb >> 1), fb & 1, adv);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // prologue: stages 0 .. NS-3 and the first half of stage NS-2 in flight
+#pragma unroll
+    for (int s = 0; s < NS - 2; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            issue_one(s, j, 0, BK);
+            issue_one(s, j, 1, BK);
+        }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        issue_one(NS - 2, j, 0, BK);
+        issue_one(NS - 2, j, 1, BK);
+    }
+    wait_vm<8 * (NS - 3) + 4>();  // stage 0 of this wave has landed
+    __syncthreads();              // ... and everyone's
+    load_frags(0, 0, 0);
+    int st_cur = 0;               // t mod NS
+    for (int t = 0; t < n_k; ++t) {
+        const int st_next = st_cur + 1 == NS ? 0 : st_cur + 1;
+        const int st_fill = st_cur == 0 ? NS - 1 : st_cur - 1;          // (t + NS - 1) mod NS
+        const int st_fill_b = st_fill == 0 ? NS - 1 : st_fill - 1;      // (t + NS - 2) mod NS
+        mfma16(0, st_fill_b, 2, t + NS - 1 < n_k ? BK : 0, st_cur, 1);
+        wait_vm<8 * (NS - 3)>();  // stage t+1 has landed; the younger ones stay in flight
+        __syncthreads();          // ... for everyone; and everyone is done with stage t-1
+        mfma16(1, st_fill, 0, t + NS < n_k ? BK : 0, st_next, 0);
+        st_cur = st_next;
+    }
+    wait_vm<0>();                 // the ring's trailing fills must not land in the staging
+
+    // ---- epilogue -----------------------------------------------------------------------
+    TileCtx ctx;
+    ctx.lane = lane; ctx.wave = wave; ctx.hh = hh; ctx.l32 = l32; ctx.wt = wt; ctx.wf = wf;
+    ctx.split = split; ctx.ft = ft; ctx.mat = mat; ctx.feat0 = feat0; ctx.row0 = row0;
+    ctx.heads_out = heads_out; ctx.out = out;
+    tile_epilogue<MODE, EXTRA>(p, acc, ctx, smem);
+}
+
+// ---------------------------------------------------------------------------------------
+// The same tile with the contraction in steps of 64 ("slabs"): every fill instruction
+// fetches whole 128-byte lines (8 rows x 128 B), which the memory pipeline serves at
+// 1.7 x the rate of the 64-byte row pieces of the kernel above and at a higher clock.
+//
+// LDS: a ring of 16 units of 8 KB; a unit is 64 rows x 128 B of one operand.  A step T
+// needs four feature units W0..W3 (tile rows 64 i ..) and four token units X0..X3, where
+// X_q holds the rows both token halves consume in quarter q of the step: tile rows
+// 32 q .. + 32 and 128 + 32 q .. + 32.  Units of step T sit in slots 8 (T & 1) + (0..7).
+// The 16-byte chunk c of unit row r is stored at position c ^ (r & 7).
+//
+// A step is 64 MFMAs per wave in four quarters; quarter q multiplies the wave's four
+// feature blocks by its token block q for all four 16-wide sub-steps.  The feature
+// operands of a whole step live in registers (loaded during the second half of the
+// previous step), so the W units of step T are free again when T begins and are refilled
+// with step T + 2 during its first two quarters; X_q is free after quarter q - 1 and is
+// refilled in quarters 2 and 3.  One barrier per quarter, two fill instructions per wave
+// and unit, one fill instruction every four MFMAs, as in the kernel above.
+// Needs an even number (>= 2) of steps per split.
+constexpr int kUnitBytes = 64 * 128;
+constexpr int kSlabLdsBytes = 16 * kUnitBytes;
+
+template <int MODE, bool EXTRA = false>
+__global__ __launch_bounds__(256) void proj_slab_kernel(ProjParams p, int n_tok_tiles,
+                                                        int n_tiles, int per_xcd) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hh = lane >> 5, l32 = lane & 31;
+    const int wt = wave >> 1, wf = wave & 1;
+
+    // ---- which tile (as above) ---------------------------------------------------------
+    int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (logical >= n_tiles * p.n_ksplit) return;
+    const int split = logical / n_tiles;
+    logical -= split * n_tiles;
+    const int n_feat_tiles = p.tile_begin[3];
+    const int per_group = kGroup * n_feat_tiles;
+    const int group = logical / per_group;
+    const int first_tok = group * kGroup;
+    const int rows_in_group = min(kGroup, n_tok_tiles - first_tok);
+    const int within = logical - group * per_group;
+    const int tok_tile = first_tok + within % rows_in_group;
+    const int ft = within / rows_in_group;
+    int mat = 0;
+    if (MODE == kProjRope) {
+        if (ft >= p.tile_begin[1]) mat = 1;
+        if (ft >= p.tile_begin[2]) mat = 2;
+    }
+    const int feat0 = (ft - p.tile_begin[mat]) * T;
+    const bf16_t* w = p.w[mat];
+    bf16_t* out = p.out[mat];
+    const int heads_out = mat == 0 ? p.hq : p.hkv;
+    const int row0 = tok_tile * T;
+
+    const int n_T = p.hid / 64 / p.n_ksplit;   // steps of this split: even, >= 2 (launcher)
+    const int k_begin = split * n_T * 64;
+
+    // ---- fill side: wave w issues instructions j = 0, 1 of every unit: unit rows
+    // 8 (2 w + j) .. + 8; lane = (row in the eight, position), fetching chunk pos ^ row
+    const int rl = lane >> 3;
+    const int gchunk = (lane & 7) ^ rl;
+    const bf16_t* wptr[4][2];
+    const bf16_t* xptr[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int ur = 8 * (2 * wave + j) + rl;   // row inside the unit
+            const int r = 64 * i + ur;                // feature row of the tile
+            if (MODE == kProjGated) {
+                const int f = ft * 128 + (r >> 7) * 64 + (r & 63);
+                wptr[i][j] = p.w[(r >> 6) & 1] + (int64_t)f * p.hid + k_begin + gchunk * 8;
+            } else {
+                wptr[i][j] = w + (int64_t)(feat0 + r) * p.hid + k_begin + gchunk * 8;
+            }
+            const int xr = ur < 32 ? 32 * i + ur : 96 + 32 * i + ur;   // token row of the tile
+            const int gr = min(row0 + xr, p.m - 1);
+            const int64_t src_row = p.row_idx ? p.row_idx[gr] : gr;
+            xptr[i][j] = p.hidden + src_row * p.hid + k_begin + gchunk * 8;
+        }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+    const uint32_t lds_fill = __builtin_amdgcn_readfirstlane(lds0 + wave * 2 * 1024);
+    // unit i of the feature (which = 1) or token (which = 0) operand of a step with
+    // parity par; adv is 64, or 0 once the last step has been requested
+    auto issue_w = [&](int par, int i, int j, int adv) {
+        dma16(wptr[i][j], lds_fill + (par * 8 + i) * kUnitBytes + j * 1024);
+        wptr[i][j] += adv;
+    };
+    auto issue_x = [&](int par, int i, int j, int adv) {
+        dma16(xptr[i][j], lds_fill + (par * 8 + 4 + i) * kUnitBytes + j * 1024);
+        xptr[i][j] += adv;
+    };
+
+    // ---- read side: byte offsets of the lane's operand pieces --------------------------
+    // feature block fb: base_w + fb * 4096; token quarter q: base_x + q * 8192
+    uint32_t base_w[2][4], base_x[2][4];
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const uint32_t swz = (uint32_t)(((2 * ks + hh) ^ (l32 & 7)) * 16);
+            base_w[par][ks] = par * 8 * kUnitBytes + 2 * wf * kUnitBytes + l32 * 128 + swz;
+            base_x[par][ks] = par * 8 * kUnitBytes + 4 * kUnitBytes + (wt * 32 + l32) * 128 + swz;
+        }
+    auto ld = [&](uint32_t off) { return *reinterpret_cast<const bf16x8*>(smem + off); };
+
+    bf16x8 fw01[2][4][2];   // [step parity][feature block][sub-step 0, 1]
+    bf16x8 fw23[4][2];      // [feature block][sub-step 2, 3]
+    bf16x8 fx[2][4];        // [quarter parity][sub-step]
+
+    f32x16 acc[4][4];   // [feature block][token block]
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fb][tb][r] = 0.f;
+
+    // ---- prologue: steps 0 and 1 requested; operands of step 0, quarter 0 loaded --------
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int adv = par + 1 < n_T ? 64 : 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) issue_w(par, i, j, adv);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) issue_x(par, i, j, adv);
+    }
+    wait_vm<22>();     // W0..W3 and X0 of step 0 (the first ten of 32 instructions) landed
+    __syncthreads();
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) {
+        fw01[0][fb][0] = ld(base_w[0][0] + fb * 4096);
+        fw01[0][fb][1] = ld(base_w[0][1] + fb * 4096);
+        fw23[fb][0] = ld(base_w[0][2] + fb * 4096);
+        fw23[fb][1] = ld(base_w[0][3] + fb * 4096);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) fx[0][ks] = ld(base_x[0][ks]);
+    __syncthreads();   // everybody holds step 0's feature operands: its W units may be refilled
+
+    // One quarter: 16 MFMAs (sub-step outer, feature block inner) on token block Q with the
+    // token operands fx[Q & 1]; after every four MFMAs one fill instruction and one token
+    // operand of the next quarter.  PAR = parity of the step.
+#define PKV_QUARTER(PAR, Q, ADV)                                                          \
+    {                                                                                     \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                \
+            _Pragma("unroll") for (int fb = 0; fb < 4; ++fb) {                            \
+                const bf16x8 a_ = ks < 2 ? fw01[PAR][fb][ks] : fw23[fb][ks - 2];          \
+                acc[fb][Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, fx[(Q) & 1][ks], \
+                                                                     acc[fb][Q], 0, 0, 0); \
+                if ((Q) == 3 && ks >= 2)   /* last use: take step T + 1's operand */      \
+                    fw23[fb][ks - 2] = ld(base_w[(PAR) ^ 1][ks] + fb * 4096);             \
+            }                                                                             \
+            __builtin_amdgcn_sched_barrier(0);                                            \
+            /* fill: quarters 0, 1 -> feature units 2 Q, 2 Q + 1; 2, 3 -> token units */  \
+            if ((Q) < 2) issue_w(PAR, 2 * (Q) + (ks >> 1), ks & 1, ADV);                  \
+            else issue_x(PAR, 2 * ((Q) - 2) + (ks >> 1), ks & 1, ADV);                    \
+            /* token operand of the next quarter (quarter 0 of the next step after 3) */  \
+            if ((Q) < 3) fx[((Q) + 1) & 1][ks] = ld(base_x[PAR][ks] + ((Q) + 1) * 8192);  \
+            else fx[0][ks] = ld(base_x[(PAR) ^ 1][ks]);                                   \
+            /* feature operands of sub-steps 0, 1 of the next step, into the other set */ \
+            if ((Q) == 2) {                                                               \
+                fw01[(PAR) ^ 1][ks][0] = ld(base_w[(PAR) ^ 1][0] + ks * 4096);            \
+                fw01[(PAR) ^ 1][ks][1] = ld(base_w[(PAR) ^ 1][1] + ks * 4096);            \
+            }                                                                             \
+            __builtin_amdgcn_sched_barrier(0);                                            \
+        }                                                                                 \
+    }
+    // outstanding fills allowed at the barrier that ends quarter 0, 1, 2, 3 (see above):
+    // what the next quarter reads was requested at least 22 / 16 / 18 / 20 instructions ago
+#define PKV_STEP(PAR, ADV)                                                                \
+    PKV_QUARTER(PAR, 0, ADV) wait_vm<22>(); __syncthreads();                              \
+    PKV_QUARTER(PAR, 1, ADV) wait_vm<16>(); __syncthreads();                              \
+    PKV_QUARTER(PAR, 2, ADV) wait_vm<18>(); __syncthreads();                              \
+    PKV_QUARTER(PAR, 3, ADV) wait_vm<20>(); __syncthreads();
+
+    for (int t = 0; t < n_T; t += 2) {
+        const int adv0 = t + 3 < n_T ? 64 : 0;   // step t fetches step t + 2
+        const int adv1 = t + 4 < n_T ? 64 : 0;
+        PKV_STEP(0, adv0)
+        PKV_STEP(1, adv1)
+    }
+#undef PKV_STEP
+#undef PKV_QUARTER
+    wait_vm<0>();                 // the ring's trailing fills must not land in the staging
+
+    TileCtx ctx;
+    ctx.lane = lane; ctx.wave = wave; ctx.hh = hh; ctx.l32 = l32; ctx.wt = wt; ctx.wf = wf;
+    ctx.split = split; ctx.ft = ft; ctx.mat = mat; ctx.feat0 = feat0; ctx.row0 = row0;
+    ctx.heads_out = heads_out; ctx.out = out;
+    tile_epilogue<MODE, EXTRA>(p, acc, ctx, smem);
+}
+
 // adds the splits of the contraction in a fixed order, rotates, rounds once, stores.
 // One thread per (row, head slot, pair index i): elements i and i + 64 of the head.
 __global__ __launch_bounds__(256) void proj_splitk_finish_kernel(ProjParams p) {
@@ -544,7 +770,10 @@ pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(proj_dma_kernel<MODE, EXTRA>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes) != hipSuccess)
+                                kLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(proj_slab_kernel<MODE, EXTRA>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kSlabLdsBytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
         configured = true;
     }
@@ -556,8 +785,13 @@ pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
     q.n_ksplit = plan_ksplit(n_tiles, p.hid / BK);
     if (q.n_ksplit > 1 && q.partial == nullptr) return PKV_ERR_WORKSPACE;
     const int per_xcd = (int)ceil_div(n_tiles * q.n_ksplit, 8);
-    hipLaunchKernelGGL((proj_dma_kernel<MODE, EXTRA>), dim3((unsigned)(per_xcd * 8)), dim3(256),
-                       kLdsBytes, st, q, n_tok_tiles, (int)n_tiles, per_xcd);
+    // contraction in slabs of 64 when every split has an even number of them
+    if (p.hid % (128 * q.n_ksplit) == 0)
+        hipLaunchKernelGGL((proj_slab_kernel<MODE, EXTRA>), dim3((unsigned)(per_xcd * 8)),
+                           dim3(256), kSlabLdsBytes, st, q, n_tok_tiles, (int)n_tiles, per_xcd);
+    else
+        hipLaunchKernelGGL((proj_dma_kernel<MODE, EXTRA>), dim3((unsigned)(per_xcd * 8)),
+                           dim3(256), kLdsBytes, st, q, n_tok_tiles, (int)n_tiles, per_xcd);
     if (q.n_ksplit > 1) {
         if (MODE == kProjRope) {
             const int64_t total = (int64_t)p.m * (T * p.tile_begin[3] / 2);
