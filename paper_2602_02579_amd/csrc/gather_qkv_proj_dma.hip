@@ -597,12 +597,18 @@ __global__ __launch_bounds__(256) void proj_slab_kernel(ProjParams p, int n_tok_
     for (int ks = 0; ks < 4; ++ks) fx[0][ks] = ld(base_x[0][ks]);
     __syncthreads();   // everybody holds step 0's feature operands: its W units may be refilled
 
-    // One quarter: 16 MFMAs (sub-step outer, feature block inner) on token block Q with the
-    // token operands fx[Q & 1]; after every four MFMAs one fill instruction and one token
-    // operand of the next quarter.  PAR = parity of the step.
+    // One quarter: 16 MFMAs in four groups (sub-step outer, feature block inner) on token
+    // block Q with the token operands fx[Q & 1]; one fill instruction after every group.
+    // The LDS reads of the quarter (token operands of the next quarter; in quarter 2 the
+    // sub-step 0, 1 feature operands of the next step into the other register set; in
+    // quarter 3 the sub-step 2, 3 ones, each right after its last use - which is why
+    // quarter 3 runs sub-steps 2, 3 first) all go out in the first three groups, so that
+    // they have returned when the barrier that ends the quarter waits for them.
+    // PAR = parity of the step.
 #define PKV_QUARTER(PAR, Q, ADV)                                                          \
     {                                                                                     \
-        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                \
+        _Pragma("unroll") for (int g_ = 0; g_ < 4; ++g_) {                                \
+            const int ks = (Q) == 3 ? (g_ + 2) & 3 : g_;                                  \
             _Pragma("unroll") for (int fb = 0; fb < 4; ++fb) {                            \
                 const bf16x8 a_ = ks < 2 ? fw01[PAR][fb][ks] : fw23[fb][ks - 2];          \
                 acc[fb][Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_, fx[(Q) & 1][ks], \
@@ -612,15 +618,22 @@ __global__ __launch_bounds__(256) void proj_slab_kernel(ProjParams p, int n_tok_
             }                                                                             \
             __builtin_amdgcn_sched_barrier(0);                                            \
             /* fill: quarters 0, 1 -> feature units 2 Q, 2 Q + 1; 2, 3 -> token units */  \
-            if ((Q) < 2) issue_w(PAR, 2 * (Q) + (ks >> 1), ks & 1, ADV);                  \
-            else issue_x(PAR, 2 * ((Q) - 2) + (ks >> 1), ks & 1, ADV);                    \
-            /* token operand of the next quarter (quarter 0 of the next step after 3) */  \
-            if ((Q) < 3) fx[((Q) + 1) & 1][ks] = ld(base_x[PAR][ks] + ((Q) + 1) * 8192);  \
-            else fx[0][ks] = ld(base_x[(PAR) ^ 1][ks]);                                   \
-            /* feature operands of sub-steps 0, 1 of the next step, into the other set */ \
+            if ((Q) < 2) issue_w(PAR, 2 * (Q) + (g_ >> 1), g_ & 1, ADV);                  \
+            else issue_x(PAR, 2 * ((Q) - 2) + (g_ >> 1), g_ & 1, ADV);                    \
+            /* token operands of the next quarter: 2, 1, 1, 0 per group */                \
+            _Pragma("unroll") for (int n_ = 0; n_ < 4; ++n_) {                            \
+                if ((n_ < 2 ? 0 : n_ - 1) != g_) continue;                                \
+                if ((Q) < 3) fx[((Q) + 1) & 1][n_] = ld(base_x[PAR][n_] + ((Q) + 1) * 8192); \
+                else fx[0][n_] = ld(base_x[(PAR) ^ 1][n_]);                               \
+            }                                                                             \
+            /* quarter 2: feature operands of sub-steps 0, 1 of the next step: blocks     \
+               0 | 1, 2 | 3 | - per group */                                              \
             if ((Q) == 2) {                                                               \
-                fw01[(PAR) ^ 1][ks][0] = ld(base_w[(PAR) ^ 1][0] + ks * 4096);            \
-                fw01[(PAR) ^ 1][ks][1] = ld(base_w[(PAR) ^ 1][1] + ks * 4096);            \
+                _Pragma("unroll") for (int fb = 0; fb < 4; ++fb) {                        \
+                    if ((fb == 0 ? 0 : fb == 3 ? 2 : 1) != g_) continue;                  \
+                    fw01[(PAR) ^ 1][fb][0] = ld(base_w[(PAR) ^ 1][0] + fb * 4096);        \
+                    fw01[(PAR) ^ 1][fb][1] = ld(base_w[(PAR) ^ 1][1] + fb * 4096);        \
+                }                                                                         \
             }                                                                             \
             __builtin_amdgcn_sched_barrier(0);                                            \
         }                                                                                 \
