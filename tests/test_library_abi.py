@@ -68,6 +68,45 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert lib.pkv_rope_restore(ctypes.byref(c2), None, None, None, 0, 5, None) == 3
 
 
+def test_glue_and_variant_entry_points_check_their_arguments_on_the_host():
+    if not os.path.exists(api.library_path()):
+        pytest.skip("libpkv.so not built")
+    import torch
+    lib = api.load_library()
+    bf = api.PKV_BF16
+    # scratch sizing: split contractions (few rows) need fp32 partials, large launches and
+    # fp32 storage do not; invalid sizes give 0
+    few = api.pkv_glue_workspace_bytes(torch.bfloat16, 128, 4096, 14336)
+    assert few > 0 and few % 256 == 0
+    assert api.pkv_glue_workspace_bytes(torch.float32, 128, 4096, 14336) == 0
+    assert api.pkv_glue_workspace_bytes(torch.bfloat16, 100000, 4096, 14336) == 0
+    assert lib.pkv_glue_workspace_bytes(bf, -1, 4096, 14336) == 0
+    # null pointers / sizes / dtype are refused before any launch; m == 0 is a no-op
+    assert lib.pkv_rmsnorm_rows(bf, None, None, None, 1e-5, None, 4, 64, None) == 1
+    assert lib.pkv_rmsnorm_rows(bf, None, None, None, 1e-5, None, 4, 60, None) == 3
+    assert lib.pkv_rmsnorm_rows(bf, None, None, None, -1.0, None, 4, 64, None) == 2
+    assert lib.pkv_rmsnorm_rows(9, None, None, None, 1e-5, None, 4, 64, None) == 3
+    assert lib.pkv_rmsnorm_rows(bf, None, None, None, 1e-5, None, 0, 64, None) == 0
+    assert lib.pkv_gather_rows(bf, None, None, None, 4, 64, None) == 1
+    assert lib.pkv_gather_rows(bf, None, None, None, 4, 63, None) == 3
+    assert lib.pkv_gather_rows(bf, None, None, None, -4, 64, None) == 2
+    assert lib.pkv_linear_rows(bf, None, None, None, None, 4, 64, 64, None, 0, None) == 1
+    assert lib.pkv_linear_rows(bf, None, None, None, None, 4, 0, 64, None, 0, None) == 2
+    assert lib.pkv_swiglu_rows(bf, None, None, None, None, 0, 64, 64, None, 0, None) == 0
+    c = api.LayerCfg(32, 8, 128, 4096, 5e5, "bf16")._c()
+    var = api._CVariant(None, None, None, 1, None, 1e-6)      # q_norm without k_norm
+    assert lib.pkv_gather_qkv_proj_ex(ctypes.byref(c), None, None, None, None, None, None,
+                                      ctypes.byref(var), None, None, None, 4, None, 0, None) == 1
+    assert lib.pkv_gather_qkv_proj_ex(ctypes.byref(c), None, None, None, None, None, None,
+                                      None, None, None, None, 0, None, 0, None) == 0
+    assert lib.pkv_gather_qkv_proj_scatter(ctypes.byref(c), None, None, None, None, None, None,
+                                           None, None, None, None, None, 5, 3, None, 0,
+                                           None) == 2          # more rows than cache rows
+    assert lib.pkv_gather_qkv_proj_scatter(ctypes.byref(c), None, None, None, None, None, None,
+                                           None, None, None, None, None, 3, 5, None, 0,
+                                           None) == 1
+
+
 def test_a_missing_library_fails_loudly_and_nothing_falls_back():
     """The binding has no CPU path: with the shared library absent, the first call
     raises (checked in a fresh interpreter so that this process keeps its library)."""
