@@ -44,6 +44,11 @@
  *   Index arrays (row_idx, dst_row, row_pos) are read on the device, so
  *   their VALUES cannot be checked by the host: out-of-range values there
  *   are undefined behaviour and are the caller's responsibility.
+ * Alignment: tensors are expected at 16-byte aligned addresses (any device
+ *   allocator gives 256).  The kernels issue 16-byte accesses; where a call
+ *   says so it accepts less (pkv_topk_select, pkv_linear_rows,
+ *   pkv_swiglu_rows fall back to narrower accesses) or refuses
+ *   (pkv_rmsnorm_rows, pkv_gather_rows).
  * Supported shapes: head_dim even, a multiple of 16 and <= 256;
  *   n_q_heads a multiple of n_kv_heads; hidden a multiple of 8.
  */
@@ -296,8 +301,9 @@ size_t pkv_workspace_bytes(int which_call, const pkv_layer_cfg* cfg,
 /*
  * y[i, :] = h[row_idx[i], :] / sqrt(mean_j h[row_idx[i], j]^2 + eps) * weight
  * for i < m; row_idx == NULL means row i.  The mean of squares and the scaling
- * are fp32.  hidden must be a multiple of 8 and at most 16384.  y must not
- * overlap h.  m == 0 is a no-op.
+ * are fp32.  hidden must be a multiple of 8 and at most 16384; h, weight and y
+ * must be 16-byte aligned (PKV_ERR_UNSUPPORTED otherwise).  y must not overlap
+ * h.  m == 0 is a no-op.
  */
 pkv_status pkv_rmsnorm_rows(int32_t dtype,
                             const void* h,          /* [>= max row + 1, hidden] */
@@ -323,7 +329,9 @@ pkv_status pkv_gather_rows(int32_t dtype,
  * y = round(x W^T), then, if residual != NULL, y = round(y + residual).
  * y may be the same buffer as residual (each element is read before it is
  * written, by the same thread); it must not overlap x or w.  k_in and n_out
- * must be multiples of 8.  Scratch: pkv_glue_workspace_bytes(dtype, m, k_in,
+ * must be multiples of 8.  Any alignment of the element type is accepted;
+ * 16-byte aligned bf16 operands with k_in a multiple of 32 and n_out a
+ * multiple of 256 take the matrix-core kernel.  Scratch: pkv_glue_workspace_bytes(dtype, m, k_in,
  * n_out); its contents are garbage afterwards.  m == 0 is a no-op.
  */
 pkv_status pkv_linear_rows(int32_t dtype,

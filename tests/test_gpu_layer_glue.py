@@ -211,3 +211,41 @@ def test_glue_at_the_benchmark_widths_on_sampled_rows(gpu_device):
         got = host(y)
         assert np.isfinite(got).all()
         assert rel_err(got[pick], MO.linear_rows(act[pick], wd, res[pick], dtype)) <= TOL[dtype]
+
+
+def test_unaligned_pointers_take_the_plain_kernels(gpu_device):
+    """Tensors whose storage is only 2-byte aligned: the tile kernel (16-byte loads) must not be
+    used; the results still match the oracle.  RMSNorm and the row gather need 16-byte alignment
+    and refuse instead."""
+    dtype, m, k_in, n_out = "bf16", 70, 512, 256
+    x = rnd(101, (m, k_in), dtype)
+    w = rnd(102, (n_out, k_in), dtype, 1.0 / np.sqrt(k_in))
+    wu = rnd(103, (n_out, k_in), dtype, 1.0 / np.sqrt(k_in))
+    res = rnd(104, (m, n_out), dtype)
+
+    def shifted(a):
+        flat = torch.zeros(a.size + 1, dtype=torch.bfloat16, device=gpu_device)
+        view = flat[1:].view(a.shape)
+        view.copy_(dev(a, dtype, gpu_device))
+        assert view.data_ptr() % 16 == 2 and view.is_contiguous()
+        return view
+    ws = ws_for(dtype, m, k_in, n_out, gpu_device)
+    y = shifted(np.zeros((m, n_out), np.float32))
+    api.pkv_linear_rows(shifted(x), shifted(w), shifted(res), y, ws)
+    assert rel_err(host(y), MO.linear_rows(x, w, res, dtype)) <= TOL[dtype]
+    api.pkv_swiglu_rows(shifted(x), shifted(w), shifted(wu), y, ws)
+    assert rel_err(host(y), MO.swiglu_up(x, w, wu, dtype)) <= TOL[dtype]
+    # one unaligned operand is enough to leave the tile kernel
+    y2 = torch.empty((m, n_out), dtype=torch.bfloat16, device=gpu_device)
+    api.pkv_linear_rows(dev(x, dtype, gpu_device), shifted(w), None, y2, ws)
+    assert rel_err(host(y2), MO.linear_rows(x, w, None, dtype)) <= TOL[dtype]
+    gain = dev(np.ones(k_in, np.float32), dtype, gpu_device)
+    out = torch.empty((m, k_in), dtype=torch.bfloat16, device=gpu_device)
+    with pytest.raises(api.PkvError) as e:
+        api.pkv_rmsnorm_rows(shifted(x), None, gain, 1e-5, out)
+    assert e.value.status == 3
+    idx = torch.arange(m, dtype=torch.int32, device=gpu_device)
+    with pytest.raises(api.PkvError) as e:
+        api.pkv_gather_rows(shifted(x), idx, out)
+    assert e.value.status == 3
+    torch.cuda.synchronize()
