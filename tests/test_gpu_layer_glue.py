@@ -249,3 +249,24 @@ def test_unaligned_pointers_take_the_plain_kernels(gpu_device):
         api.pkv_gather_rows(shifted(x), idx, out)
     assert e.value.status == 3
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rmsnorm_degenerate_rows(gpu_device, dtype):
+    """An all-zero row stays zero (no 0/0), a huge row and a tiny row normalise like any other."""
+    hidden = 4096
+    h = rnd(111, (6, hidden), dtype)
+    h[0] = 0.0
+    h[1] = synth.to_storage(h[1] * np.float32(2.0 ** 40), dtype)      # squares near 2^80
+    h[2] = synth.to_storage(h[2] * np.float32(2.0 ** -40), dtype)     # far below eps
+    h[3] = 0.0
+    h[3, 17] = 1.0                                                     # a single spike
+    w = synth.to_storage(np.linspace(0.5, 1.5, hidden).astype(np.float32), dtype)
+    want = MO.rmsnorm_rows(h, None, w, 1e-6, dtype)
+    y = torch.full((6, hidden), float("nan"), dtype=TDT[dtype], device=gpu_device)
+    api.pkv_rmsnorm_rows(dev(h, dtype, gpu_device), None, dev(w, dtype, gpu_device), 1e-6, y)
+    got = host(y)
+    assert np.isfinite(got).all()
+    assert np.all(got[0] == 0.0)
+    for r in range(6):
+        assert rel_err(got[r], want[r]) <= TOL[dtype] or np.abs(want[r]).max() < 1e-30, r
