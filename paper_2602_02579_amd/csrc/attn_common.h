@@ -18,6 +18,8 @@ struct AttnParams {
     float* part_ml;          // [n_splits, m*hq, 2] (max in raw logits, sum) or nullptr
     int* flags;              // [n_tiles, hkv]: written by the pipelined kernel (1 = redo the
                              // tile), read by the exact kernel when not nullptr
+    int* queue;              // [hkv] next unclaimed row tile per kv head, zero before the
+                             // launch (pipelined kernel only)
     int m, n_keys, n_pad, hq, hkv, group, bm, n_tiles, n_splits, split_len;
     int fixed_limit;         // >= 0: every row sees keys 0..fixed_limit
     float scale_log2;        // softmax scale * log2(e)

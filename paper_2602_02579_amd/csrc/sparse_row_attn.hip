@@ -392,8 +392,10 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(
     const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int n_keys, int n_pad,
     int hkv, int d, int* marked) {
     __shared__ bf16_t tile[64][64 + 2];
-    // this pre-pass also clears the count of tiles marked for the repair pass
-    if (marked && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *marked = 0;
+    // this pre-pass also clears the count of tiles marked for the repair pass and the
+    // work-queue counters behind it
+    if (marked && blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = threadIdx.x; i <= hkv; i += 256) marked[i] = 0;
     const int t0 = blockIdx.x * 64;
     const int c0 = blockIdx.y * 64;  // column in the flattened [hkv * D] axis
     const int tid = threadIdx.x;
@@ -433,14 +435,16 @@ bool mfma_attn_supported(const pkv_layer_cfg& cfg) {
 int64_t pad64(int64_t n) { return (n + 63) & ~(int64_t)63; }
 
 // workspace: V^T [hkv, D, n_pad] (rounded up to 256 bytes), then one int per
-// (row tile, kv head) for the repair pass
+// (row tile, kv head) for the repair pass, the count of marked tiles, and one work-queue
+// counter per kv head
 size_t attn_vt_bytes(const pkv_layer_cfg& cfg, int64_t n_keys) {
     const size_t b = (size_t)cfg.n_kv_heads * cfg.head_dim * pad64(n_keys) * sizeof(bf16_t);
     return (b + 255) & ~(size_t)255;
 }
 size_t attn_flag_bytes(const pkv_layer_cfg& cfg, int64_t m) {
     const int bm = 256 / (cfg.n_q_heads / cfg.n_kv_heads);
-    return ((size_t)ceil_div(m, bm) * cfg.n_kv_heads + 1) * sizeof(int);   // + marked count
+    // + marked count + one work-queue counter per kv head
+    return ((size_t)ceil_div(m, bm) * cfg.n_kv_heads + 1 + cfg.n_kv_heads) * sizeof(int);
 }
 
 template <int D, bool kPV>
@@ -540,6 +544,7 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         // pipelined kernel with a fixed softmax reference per column, then the exact
         // kernel on the tiles it marked (normally none: those workgroups exit at once)
         p.flags = reinterpret_cast<int*>((unsigned char*)ws + attn_vt_bytes(cfg, n_keys));
+        p.queue = p.flags + p.n_tiles * p.hkv + 1;
         const pkv_status rc = launch_attn_dma128(p, st);
         if (rc != PKV_OK) return rc;
         return launch_attn_mfma<128, true>(p, st);

@@ -27,6 +27,8 @@
 // * The reference maximum of a column is fixed after its first 32 keys (see
 //   PKV_ACC): no maximum, no rescaling and no branch in the hot loop; tiles whose
 //   probabilities leave the safe range are marked and redone by the exact kernel.
+#include <algorithm>
+
 #include "attn_common.h"
 
 namespace pkv {
@@ -40,6 +42,7 @@ constexpr int NS = 4;                  // LDS stages per operand
 constexpr int kStageK = kBN * D * 2;   // bytes: 64 keys x 256 B
 constexpr int kStageV = D * kBN * 2;   // bytes: 128 d-rows x 128 B
 constexpr int kLdsBytes = NS * (kStageK + kStageV);
+constexpr int kStealLag = 2;   // tiles another kv head must be behind before a workgroup helps it
 
 // 16 bytes per lane from global memory straight into LDS: lane i of the wave
 // writes LDS bytes [lds_base + 16 i, +16); lds_base must be wave-uniform.
@@ -76,12 +79,48 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     const int hh = lane >> 5;
     const int l32 = lane & 31;
 
-    // kv head fastest: with 8 kv heads a head stays on one XCD and its K/V
-    // stream is shared through that XCD's L2; heaviest row tiles first
-    int wg = blockIdx.x;
-    const int g = wg % p.hkv;
-    wg /= p.hkv;
-    const int tile = p.n_tiles - 1 - wg;
+    // Work distribution.  The launch is one workgroup per CU and every workgroup claims
+    // (kv head, row tile) pairs until none are left: a row tile costs about one unit per
+    // 64 keys below its largest limit, so with rows in position order the costs rise
+    // linearly, there are only a few tiles per CU, and the CUs (and the XCDs, which do not
+    // all run at the same speed) finish far apart when the hardware hands out whole
+    // workgroups; claiming the next tile also costs much less than starting a workgroup.
+    // Each kv head has a counter; tiles are claimed heaviest first.  Workgroup b starts
+    // with head b mod hkv - with 8 kv heads that head's K/V stream is then shared through
+    // the L2 of the XCD the workgroup runs on - and moves on to the following heads once
+    // its own has nothing left.
+    __shared__ int s_job;
+    const int home = blockIdx.x % p.hkv;
+  for (;;) {
+    if (tid == 0) {
+        int job = -1;
+        // at most hkv failed claims: each one finds a head exhausted for good
+        for (int attempt = 0; attempt <= p.hkv && job < 0; ++attempt) {
+            int best = home;
+            int best_c = __hip_atomic_load(&p.queue[home], __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+            if (best_c < p.n_tiles) best_c -= kStealLag;   // prefer the own head
+            for (int q = 1; q < p.hkv; ++q) {
+                int y = home + q;
+                if (y >= p.hkv) y -= p.hkv;
+                const int c = __hip_atomic_load(&p.queue[y], __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+                if (c < best_c) {
+                    best_c = c;
+                    best = y;
+                }
+            }
+            if (best_c >= p.n_tiles) break;   // nothing left anywhere
+            const int j = atomicAdd(&p.queue[best], 1);
+            if (j < p.n_tiles) job = best * p.n_tiles + j;
+        }
+        s_job = job;
+    }
+    __syncthreads();
+    const int job = __builtin_amdgcn_readfirstlane(s_job);
+    if (job < 0) break;   // block-uniform: every head is exhausted
+    const int g = job / p.n_tiles;
+    const int tile = p.n_tiles - 1 - job % p.n_tiles;
 
     int limit[2], row[2], head[2];
     bool valid[2];
@@ -115,7 +154,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     const int n_iter = __builtin_amdgcn_readfirstlane((key_end + kBN - 1) / kBN);
     if (n_iter <= 0) {        // block-uniform: the tile has no valid row
         if (tid == 0) p.flags[tile * p.hkv + g] = 0;
-        return;
+        continue;
     }
     // sub-steps [0, u_unm) lie entirely at or below every limit of this wave.  A wave
     // without any valid column (the ragged last row tile) has nothing to mask: whatever
@@ -477,13 +516,15 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
             }
         if (p.lse && hh == 0) p.lse[colg] = m_run[cb] * p.scale + logf(l_tot[cb]);
     }
+  }   // next (kv head, row tile)
 }
 
 }  // namespace
 
 pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
     // every workgroup reports through p.flags; the operands must all be there
-    if (!p.q || !p.k || !p.vt || !p.row_pos || !p.out || !p.flags) return PKV_ERR_NULL;
+    if (!p.q || !p.k || !p.vt || !p.row_pos || !p.out || !p.flags || !p.queue)
+        return PKV_ERR_NULL;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dma128_kernel),
@@ -492,7 +533,17 @@ pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
             return PKV_ERR_LAUNCH;
         configured = true;
     }
-    const int64_t grid = (int64_t)p.n_tiles * p.hkv;
+    static int n_cu = 0;   // per process; the devices of one machine are alike
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            v <= 0)
+            return PKV_ERR_LAUNCH;
+        n_cu = v;
+    }
+    // one workgroup per CU (its LDS admits no second one), or per tile if there are fewer
+    const int64_t grid = std::min<int64_t>((int64_t)p.n_tiles * p.hkv, n_cu);
     hipLaunchKernelGGL(attn_dma128_kernel, dim3((unsigned)grid), dim3(kAttnThreads),
                        kLdsBytes, st, p);
     return launch_status();

@@ -309,6 +309,41 @@ def test_sparse_row_attn_matches_oracle(gpu_device, dtype, m, n_keys, hq, hkv, d
     assert rel_err(host(out2), want[perm]) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("hq,hkv,m,n_keys", [(16, 16, 4400, 600), (32, 8, 2200, 900)])
+def test_sparse_row_attn_more_row_tiles_than_workgroups(gpu_device, hq, hkv, m, n_keys):
+    """More (kv head, row tile) pairs than the launch has workgroups, so that every
+    workgroup claims several and the heads run out at different times; rows in no
+    particular order, so that the tiles differ in cost.  Who claims a tile must not
+    matter: a second call gives the same bits."""
+    dtype, d = "bf16", 128
+    cfg = lcfg(dtype, hq, hkv, d)
+    g = np.random.default_rng(41)
+    q = rnd(42, (m, hq, d), dtype, 1.2)
+    kc, vc = rnd(43, (n_keys, hkv, d), dtype), rnd(44, (n_keys, hkv, d), dtype)
+    pos = g.integers(0, n_keys, m).astype(np.int32)
+    pos[:300] = np.sort(pos[:300])          # a few cheap tiles among the expensive ones
+    pos[:300] //= 8
+    pos[-1] = n_keys - 1
+    n_tiles = -(-m // (256 // (hq // hkv)))
+    props = torch.cuda.get_device_properties(gpu_device)
+    assert n_tiles * hkv > props.multi_processor_count
+    want, want_lse = O.sparse_row_attn(q.astype(np.float64), kc.astype(np.float64),
+                                       vc.astype(np.float64), pos, dtype=dtype)
+    out = torch.empty((m, hq, d), dtype=torch.bfloat16, device=gpu_device)
+    lse = torch.empty((m, hq), dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, m), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    args = (dev(q, dtype, gpu_device), dev(kc, dtype, gpu_device), dev(vc, dtype, gpu_device),
+            torch.from_numpy(pos).to(gpu_device))
+    api.pkv_sparse_row_attn(cfg, *args, out, lse, ws=ws)
+    assert rel_err(host(out), want) <= TOL[dtype]
+    assert np.abs(host(lse) - want_lse).max() <= 4e-3
+    out2, lse2 = torch.empty_like(out), torch.empty_like(lse)
+    ws.fill_(0xff)                           # the call must not rely on what the last one left
+    api.pkv_sparse_row_attn(cfg, *args, out2, lse2, ws=ws)
+    assert torch.equal(out, out2) and torch.equal(lse, lse2)
+
+
 def test_sparse_row_attn_closed_forms(gpu_device):
     dtype, hq, hkv, d, n_keys = "bf16", 8, 2, 128, 500
     cfg = lcfg(dtype, hq, hkv, d)
