@@ -195,14 +195,42 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
     wait_vm<4 * (NS - 4)>();   // tile 2
     __syncthreads();
 
+    // exponents of the two keys of column (CB, R) of the tile in S
+#define PKV_SCORE_PREP(S, CB, R, RAGGED)                                                 \
+    {                                                                                    \
+        float x0_ = S[CB][0][R], x1_ = S[CB][1][R];                                      \
+        if (PASS == 1 && (RAGGED)) {                                                     \
+            if (t0_ + l32 >= key_end) x0_ = -INFINITY;                                   \
+            if (t0_ + 32 + l32 >= key_end) x1_ = -INFINITY;                              \
+        }                                                                                \
+        const float ref_ = PASS == 1 ? msc[CB][R] : norm[CB][R];                         \
+        xa_ = x0_ * c2 - ref_;                                                           \
+        xb_ = x1_ * c2 - ref_;                                                           \
+    }
+    // the pending pair of probabilities (pe0_, pe1_) belongs to column (CB, R)
+#define PKV_SCORE_ADD(CB, R)                                                             \
+    {                                                                                    \
+        if (PASS == 1) {                                                                 \
+            lsum[CB][R] += tsum[CB][R];   /* the previous tile's sum */                  \
+            tsum[CB][R] = pe0_ + pe1_;                                                   \
+            tmax_ = fmaxf(tmax_, tsum[CB][R]);                                           \
+            asm volatile("" : "+v"(lsum[CB][R]), "+v"(tsum[CB][R]), "+v"(tmax_));        \
+        } else {                                                                         \
+            ksum[0] += pe0_;                                                             \
+            ksum[1] += pe1_;                                                             \
+            asm volatile("" : "+v"(ksum[0]), "+v"(ksum[1]));                             \
+        }                                                                                \
+    }
+
     // One tile: CUR = S(T) is turned into sums while NXT = S(T+1) is formed from the
     // operands in kf, which are replaced by those of tile T+2 as they fall free.
-#define PKV_SCORE_TILE(CUR, NXT, T)                                                      \
+#define PKV_SCORE_TILE(CUR, NXT, T, RAGGED)                                                      \
     {                                                                                    \
         const int t0_ = key_begin + (T) * kTile;                                         \
-        const bool ragged_ = t0_ + kTile > key_end;                                      \
         dma_tile((T) + NS - 1);                                                          \
-        bool bad_ = false;                                                               \
+        float tmax_ = 0.f;   /* largest pair sum of the tile (pass 1) */                 \
+        float xa_, xb_, pe0_ = 0.f, pe1_ = 0.f;                                          \
+        PKV_SCORE_PREP(CUR, 0, 0, RAGGED)                                                \
         _Pragma("unroll") for (int kc = 0; kc < KC; ++kc) {                              \
             _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) {                           \
                 const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,               \
@@ -214,30 +242,31 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
                     load_kf((T) + 2, 0, kc);                                             \
                     load_kf((T) + 2, 1, kc);                                             \
                 }                                                                        \
-                /* softmax step: column (scb_, sr_), keys of both key blocks */          \
+                /* softmax step: column (scb_, sr_), keys of both key blocks.  The    */ \
+                /* exponents were formed one step earlier and the results are added   */ \
+                /* one step later, so nothing waits on the transcendental unit.       */ \
                 const int step_ = kc * 4 + q4, scb_ = step_ >> 4, sr_ = step_ & 15;      \
-                float x0_ = CUR[scb_][0][sr_], x1_ = CUR[scb_][1][sr_];                  \
-                if (PASS == 1) {                                                         \
-                    if (ragged_) {                                                       \
-                        if (t0_ + l32 >= key_end) x0_ = -INFINITY;                       \
-                        if (t0_ + 32 + l32 >= key_end) x1_ = -INFINITY;                  \
-                    }                                                                    \
-                    const float e0_ = __builtin_amdgcn_exp2f(x0_ * c2 - msc[scb_][sr_]); \
-                    const float e1_ = __builtin_amdgcn_exp2f(x1_ * c2 - msc[scb_][sr_]); \
-                    lsum[scb_][sr_] += tsum[scb_][sr_];   /* the previous tile's sum */   \
-                    tsum[scb_][sr_] = e0_ + e1_;                                         \
-                    bad_ = bad_ || !(tsum[scb_][sr_] < kGrow);                           \
-                    asm volatile("" : "+v"(lsum[scb_][sr_]), "+v"(tsum[scb_][sr_]));     \
-                } else {                                                                 \
-                    ksum[0] += __builtin_amdgcn_exp2f(x0_ * c2 - norm[scb_][sr_]);       \
-                    ksum[1] += __builtin_amdgcn_exp2f(x1_ * c2 - norm[scb_][sr_]);       \
-                    asm volatile("" : "+v"(ksum[0]), "+v"(ksum[1]));                     \
+                const float e0_ = __builtin_amdgcn_exp2f(xa_);                           \
+                const float e1_ = __builtin_amdgcn_exp2f(xb_);                           \
+                if (step_ < 31) {                                                        \
+                    const int ncb_ = (step_ + 1) >> 4, nr_ = (step_ + 1) & 15;           \
+                    PKV_SCORE_PREP(CUR, ncb_, nr_, RAGGED)                               \
                 }                                                                        \
+                if (step_ > 0) {                                                         \
+                    const int pcb_ = (step_ - 1) >> 4, pr_ = (step_ - 1) & 15;           \
+                    PKV_SCORE_ADD(pcb_, pr_)                                             \
+                }                                                                        \
+                pe0_ = e0_;                                                              \
+                pe1_ = e1_;                                                              \
+                (void)scb_; (void)sr_;                                                   \
+                asm volatile("" : "+v"(pe0_), "+v"(pe1_), "+v"(xa_), "+v"(xb_));         \
                 __builtin_amdgcn_sched_barrier(0);                                       \
             }                                                                            \
         }                                                                                \
+        PKV_SCORE_ADD(1, 15)                                                             \
         if (PASS == 1) {                                                                 \
-            if (__builtin_expect(__any(bad_), 0)) {                                      \
+            /* an infinite sum shows here too; a NaN does not, and needs no rescue */  \
+            if (__builtin_expect(__any(!(tmax_ < kGrow)), 0)) {                          \
                 /* some sum left the safe range: raise the references to this tile's  */ \
                 /* maxima where they are larger, rescale, form the tile's sums again  */ \
                 _Pragma("unroll") for (int cb = 0; cb < 2; ++cb)                         \
@@ -286,14 +315,25 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
             }
     }
 
+    // only the last tile of a split can reach past key_end
+    const bool last_ragged = key_begin + n_iter * kTile > key_end;
     int T = 0;
-    for (; T + 1 < n_iter; T += 2) {
-        PKV_SCORE_TILE(s_a, s_b, T)
-        PKV_SCORE_TILE(s_b, s_a, T + 1)
+    for (; T + 2 < n_iter; T += 2) {
+        PKV_SCORE_TILE(s_a, s_b, T, false)
+        PKV_SCORE_TILE(s_b, s_a, T + 1, false)
     }
-    if (T < n_iter) PKV_SCORE_TILE(s_a, s_b, T)
+    if (T + 2 == n_iter) {
+        PKV_SCORE_TILE(s_a, s_b, T, false)
+        if (last_ragged) PKV_SCORE_TILE(s_b, s_a, T + 1, true)
+        else PKV_SCORE_TILE(s_b, s_a, T + 1, false)
+    } else {
+        if (last_ragged) PKV_SCORE_TILE(s_a, s_b, T, true)
+        else PKV_SCORE_TILE(s_a, s_b, T, false)
+    }
     wait_vm<0>();   // nothing may still be writing LDS when the workgroup retires
 #undef PKV_SCORE_TILE
+#undef PKV_SCORE_PREP
+#undef PKV_SCORE_ADD
 
     // ---- pass 1 epilogue: the 32 key lanes of a column meet through LDS -----------------------
     if (PASS == 1) {
