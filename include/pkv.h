@@ -23,7 +23,9 @@
  *   allocates nothing, frees nothing and keeps no pointer after the call
  *   returns.  Scratch memory is caller-provided (`ws`, `ws_bytes`), sized by
  *   pkv_workspace_bytes(), 256-byte aligned, and may be reused between calls
- *   on the same stream.
+ *   on the same stream.  Calls that can be in flight at the same time
+ *   (different streams) need workspaces of their own: the kernels keep
+ *   partial results, flags and work counters there.
  * Layout: token-major, contiguous.  Keys/values [tokens, n_kv_heads,
  *   head_dim]; queries/outputs [rows, n_q_heads, head_dim]; hidden states
  *   [tokens, hidden]; weights [out_features, hidden] (row-major, so both

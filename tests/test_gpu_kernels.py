@@ -280,7 +280,8 @@ def test_gather_qkv_proj_matches_oracle(gpu_device, dtype, m, hq, hkv, d, hid, t
 @pytest.mark.parametrize("dtype,m,n_keys,hq,hkv,d", [
     ("f32", 220, 1040, 4, 4, 64), ("f32", 19, 130, 4, 2, 32),
     ("bf16", 333, 2048 + 61, 32, 8, 128), ("bf16", 70, 300, 4, 4, 64),
-    ("bf16", 100, 777, 10, 2, 128), ("bf16", 1, 1, 32, 8, 128)])
+    ("bf16", 100, 777, 10, 2, 128), ("bf16", 1, 1, 32, 8, 128),
+    ("bf16", 300, 500, 4, 1, 128), ("bf16", 150, 321, 6, 3, 128), ("bf16", 90, 200, 48, 3, 128)])
 def test_sparse_row_attn_matches_oracle(gpu_device, dtype, m, n_keys, hq, hkv, d):
     cfg = lcfg(dtype, hq, hkv, d)
     g = np.random.default_rng(19)
