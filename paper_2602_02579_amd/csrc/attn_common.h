@@ -20,6 +20,10 @@ struct AttnParams {
                              // tile), read by the exact kernel when not nullptr
     int* queue;              // [hkv] next unclaimed row tile per kv head, zero before the
                              // launch (pipelined kernel only)
+    float* part_o;           // [dma_splits, m, hq, D] normalised partial outputs, and
+    float* part_lse;         // [dma_splits, m, hq] their log-sum-exp (pipelined kernel with
+                             // dma_splits > 1 only)
+    int dma_splits, dma_split_len;   // key ranges per row tile in the pipelined kernel
     int m, n_keys, n_pad, hq, hkv, group, bm, n_tiles, n_splits, split_len;
     int fixed_limit;         // >= 0: every row sees keys 0..fixed_limit
     float scale_log2;        // softmax scale * log2(e)

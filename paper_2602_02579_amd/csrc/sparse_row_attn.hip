@@ -4,6 +4,8 @@
 // selected tokens; Sec. 5.3, this attention dominates the cost; Eq. 1.)
 //
 //   out[i,h] = sum_{t <= row_pos[i]} softmax_t(q[i,h] . K[t,g(h)] * scale) V[t,g(h)]
+#include <algorithm>
+
 #include "attn_common.h"
 
 namespace pkv {
@@ -390,12 +392,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
 // 64 x 64 tiles through LDS; reads and writes are both 16-byte, coalesced.
 __global__ __launch_bounds__(256) void transpose_v_kernel(
     const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int n_keys, int n_pad,
-    int hkv, int d, int* marked) {
+    int hkv, int d, int* zero, int n_zero) {
     __shared__ bf16_t tile[64][64 + 2];
-    // this pre-pass also clears the count of tiles marked for the repair pass and the
-    // work-queue counters behind it
-    if (marked && blockIdx.x == 0 && blockIdx.y == 0)
-        for (int i = threadIdx.x; i <= hkv; i += 256) marked[i] = 0;
+    // this pre-pass also clears what the attention kernel expects at zero: the count of
+    // tiles marked for the repair pass, the work-queue counters and, when the keys are
+    // split, the marks themselves
+    if (zero && blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = threadIdx.x; i < n_zero; i += 256) zero[i] = 0;
     const int t0 = blockIdx.x * 64;
     const int c0 = blockIdx.y * 64;  // column in the flattened [hkv * D] axis
     const int tid = threadIdx.x;
@@ -444,7 +447,45 @@ size_t attn_vt_bytes(const pkv_layer_cfg& cfg, int64_t n_keys) {
 size_t attn_flag_bytes(const pkv_layer_cfg& cfg, int64_t m) {
     const int bm = 256 / (cfg.n_q_heads / cfg.n_kv_heads);
     // + marked count + one work-queue counter per kv head
-    return ((size_t)ceil_div(m, bm) * cfg.n_kv_heads + 1 + cfg.n_kv_heads) * sizeof(int);
+    const size_t b = ((size_t)ceil_div(m, bm) * cfg.n_kv_heads + 1 + cfg.n_kv_heads) * sizeof(int);
+    return (b + 255) & ~(size_t)255;
+}
+
+// Key ranges per row tile for the pipelined kernel.  With fewer (kv head, row tile) pairs
+// than CUs - Stage I's 128 query rows make 16 - every pair is cut along the keys into up to
+// 16 ranges (at least 1024 keys each, multiples of 64) so that the jobs fill the CUs of a
+// 256-CU part in as few rounds per unit of work as possible; the jobs write normalised
+// partial results that a small kernel merges.
+void attn_plan_splits(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m, int* n_splits,
+                      int* split_len) {
+    const int bm = 256 / (cfg.n_q_heads / cfg.n_kv_heads);
+    const int64_t jobs = ceil_div(m, bm) * cfg.n_kv_heads;
+    *n_splits = 1;
+    *split_len = (int)pad64(n_keys);
+    if (cfg.head_dim != 128 || jobs >= 256 || jobs <= 0) return;
+    // rounds of a 256-CU part per unit of work, with 3 % per extra range for the extra
+    // prologues and the merge: the count that minimises it
+    const int64_t most = std::min<int64_t>(16, n_keys / 1024);
+    int64_t want = 1;
+    double best = 1e30;
+    for (int64_t sp = 1; sp <= most; ++sp) {
+        const double cost = (double)ceil_div(jobs * sp, 256) / sp * (1.0 + 0.03 * (sp - 1));
+        if (cost < best - 1e-9) {
+            best = cost;
+            want = sp;
+        }
+    }
+    if (want <= 1) return;
+    const int64_t len = pad64(ceil_div(n_keys, want));
+    *split_len = (int)len;
+    *n_splits = (int)ceil_div(n_keys, len);
+}
+size_t attn_partial_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m) {
+    int n_splits, split_len;
+    attn_plan_splits(cfg, n_keys, m, &n_splits, &split_len);
+    if (n_splits <= 1) return 0;
+    const size_t cols = (size_t)m * cfg.n_q_heads;
+    return (size_t)n_splits * cols * (cfg.head_dim + 1) * sizeof(float);
 }
 
 template <int D, bool kPV>
@@ -469,7 +510,8 @@ pkv_status launch_attn_mfma(const AttnParams& p, hipStream_t st) {
 
 size_t sparse_row_attn_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m) {
     if (!mfma_attn_supported(cfg)) return 0;
-    return attn_vt_bytes(cfg, n_keys) + attn_flag_bytes(cfg, m);
+    return attn_vt_bytes(cfg, n_keys) + attn_flag_bytes(cfg, m) +
+           attn_partial_bytes(cfg, n_keys, m);
 }
 
 // Per-column (max, sum) partials of softmax(q k^T * scale) over keys
@@ -510,15 +552,18 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
     if (mfma_attn_supported(cfg)) {
         const int n_pad = (int)pad64(n_keys);
         bf16_t* vt = (bf16_t*)ws;
+        int* const ints = reinterpret_cast<int*>((unsigned char*)ws + attn_vt_bytes(cfg, n_keys));
+        const int n_flags =
+            (int)ceil_div(m, 256 / (cfg.n_q_heads / cfg.n_kv_heads)) * cfg.n_kv_heads;
+        int n_splits = 1, split_len = n_pad;
+        attn_plan_splits(cfg, n_keys, m, &n_splits, &split_len);
+        // cleared by the pre-pass: marked count + queue counters, and the marks when split
+        int* zero = d == 128 ? (n_splits > 1 ? ints : ints + n_flags) : nullptr;
+        const int n_zero = (n_splits > 1 ? n_flags : 0) + 1 + cfg.n_kv_heads;
         hipLaunchKernelGGL(transpose_v_kernel,
                            dim3((unsigned)(n_pad / 64), (unsigned)(cfg.n_kv_heads * d / 64)),
                            dim3(256), 0, st, (const bf16_t*)v_cache, vt, (int)n_keys, n_pad,
-                           cfg.n_kv_heads, d,
-                           d == 128 ? reinterpret_cast<int*>((unsigned char*)ws +
-                                                             attn_vt_bytes(cfg, n_keys)) +
-                                          ceil_div(m, 256 / (cfg.n_q_heads / cfg.n_kv_heads)) *
-                                              cfg.n_kv_heads
-                                    : nullptr);
+                           cfg.n_kv_heads, d, zero, n_zero);
         if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
         AttnParams p = {};
         p.q = (const bf16_t*)q;
@@ -543,8 +588,15 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         if (d != 128) return launch_attn_mfma<64, true>(p, st);
         // pipelined kernel with a fixed softmax reference per column, then the exact
         // kernel on the tiles it marked (normally none: those workgroups exit at once)
-        p.flags = reinterpret_cast<int*>((unsigned char*)ws + attn_vt_bytes(cfg, n_keys));
+        p.flags = ints;
         p.queue = p.flags + p.n_tiles * p.hkv + 1;
+        p.dma_splits = n_splits;
+        p.dma_split_len = split_len;
+        if (n_splits > 1) {
+            p.part_o = reinterpret_cast<float*>((unsigned char*)ws + attn_vt_bytes(cfg, n_keys) +
+                                                attn_flag_bytes(cfg, m));
+            p.part_lse = p.part_o + (size_t)n_splits * m * cfg.n_q_heads * d;
+        }
         const pkv_status rc = launch_attn_dma128(p, st);
         if (rc != PKV_OK) return rc;
         return launch_attn_mfma<128, true>(p, st);

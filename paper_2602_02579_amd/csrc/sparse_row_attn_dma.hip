@@ -91,6 +91,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     // its own has nothing left.
     __shared__ int s_job;
     const int home = blockIdx.x % p.hkv;
+    const int jobs_per_head = p.n_tiles * p.dma_splits;
   for (;;) {
     if (tid == 0) {
         int job = -1;
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
             int best = home;
             int best_c = __hip_atomic_load(&p.queue[home], __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);
-            if (best_c < p.n_tiles) best_c -= kStealLag;   // prefer the own head
+            if (best_c < jobs_per_head) best_c -= kStealLag;   // prefer the own head
             for (int q = 1; q < p.hkv; ++q) {
                 int y = home + q;
                 if (y >= p.hkv) y -= p.hkv;
@@ -110,17 +111,24 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
                     best = y;
                 }
             }
-            if (best_c >= p.n_tiles) break;   // nothing left anywhere
+            if (best_c >= jobs_per_head) break;   // nothing left anywhere
             const int j = atomicAdd(&p.queue[best], 1);
-            if (j < p.n_tiles) job = best * p.n_tiles + j;
+            if (j < jobs_per_head) job = best * jobs_per_head + j;
         }
         s_job = job;
     }
     __syncthreads();
     const int job = __builtin_amdgcn_readfirstlane(s_job);
     if (job < 0) break;   // block-uniform: every head is exhausted
-    const int g = job / p.n_tiles;
-    const int tile = p.n_tiles - 1 - job % p.n_tiles;
+    const int g = job / jobs_per_head;
+    const int within = job - g * jobs_per_head;
+    const int tile = p.n_tiles - 1 - within / p.dma_splits;
+    // With few row tiles the keys of a tile are cut into dma_splits ranges, one job each
+    // (normalised partial outputs, merged afterwards).  Everything below works in key
+    // positions relative to the start of the job's range.
+    const int split = within % p.dma_splits;
+    const int kb = split * p.dma_split_len;                      // a multiple of kBN
+    const int n_keys_job = min(p.n_keys - kb, p.dma_split_len);  // keys the job may touch
 
     int limit[2], row[2], head[2];
     bool valid[2];
@@ -134,7 +142,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         valid[cb] = rl < p.bm && row[cb] < p.m;
         limit[cb] = -1;
         if (valid[cb]) {
-            limit[cb] = p.row_pos[row[cb]];
+            limit[cb] = p.row_pos[row[cb]] - kb;   // may be negative: nothing to see here
             lmax = max(lmax, limit[cb]);
             lmin = min(lmin, limit[cb]);
         }
@@ -148,12 +156,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     int tile_max = -1;
 #pragma unroll
     for (int w = 0; w < kAttnThreads / 64; ++w) tile_max = max(tile_max, s_red[w]);
-    const int key_end = min(tile_max + 1, p.n_keys);
+    const int key_end = min(tile_max + 1, n_keys_job);
     // (wave-uniform values are moved to scalar registers explicitly: they feed
     // the scalar operands of the global->LDS loads and the loop control)
     const int n_iter = __builtin_amdgcn_readfirstlane((key_end + kBN - 1) / kBN);
-    if (n_iter <= 0) {        // block-uniform: the tile has no valid row
-        if (tid == 0) p.flags[tile * p.hkv + g] = 0;
+    if (n_iter <= 0) {        // block-uniform: no valid row, or no row reaches this range
+        if (tid == 0 && p.dma_splits == 1) p.flags[tile * p.hkv + g] = 0;
         continue;
     }
     // sub-steps [0, u_unm) lie entirely at or below every limit of this wave.  A wave
@@ -209,8 +217,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     }
     const uint32_t lds_k_wave = __builtin_amdgcn_readfirstlane(lds_k + wave * 16 * 256);
     const uint32_t lds_v_wave = __builtin_amdgcn_readfirstlane(lds_v + wave * 32 * 128);
-    const bf16_t* const k_head = p.k + (int64_t)g * D;
-    const bf16_t* const v_head = p.vt + (int64_t)g * D * p.n_pad;
+    const bf16_t* const k_head = p.k + ((int64_t)kb * p.hkv + g) * D;
+    const bf16_t* const v_head = p.vt + (int64_t)g * D * p.n_pad + kb;
 
     // K tile t (clamped to the last tile) into stage st
 #define PKV_DMA_K(T, ST)                                                                 \
@@ -219,12 +227,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         const int t0_ = t_ * kBN;                                                        \
         const bf16_t* gb_ = k_head + (int64_t)t0_ * p.hkv * D;                           \
         const uint32_t lb_ = lds_k_wave + (ST) * kStageK;                                \
-        if (t0_ + kBN <= p.n_keys) {                                                     \
+        if (t0_ + kBN <= n_keys_job) {                                                   \
             _Pragma("unroll") for (int i = 0; i < 4; ++i)                                \
                 dma16(gb_, voff_k[i], lb_ + i * 1024);                                   \
         } else { /* last, ragged tile: rows past the cache re-read its last row */      \
             _Pragma("unroll") for (int i = 0; i < 4; ++i) {                              \
-                const int r_ = min(krow[i], p.n_keys - 1 - t0_);                         \
+                const int r_ = min(krow[i], n_keys_job - 1 - t0_);                       \
                 dma16(gb_, (uint32_t)r_ * k_row_bytes + kchunk16[i], lb_ + i * 1024);    \
             }                                                                            \
         }                                                                                \
@@ -248,7 +256,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
     bool k_full_;
     uint32_t kofs_last[4];
     {
-        const int last_ = (p.n_keys - 1) % kBN;
+        const int last_ = (n_keys_job - 1) % kBN;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             kofs_last[i] = (uint32_t)min(krow[i], last_) * k_row_bytes + kchunk16[i];
@@ -258,7 +266,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         const int tk_ = min((J) + 3, n_iter - 1);                                        \
         const int t0k_ = tk_ * kBN;                                                      \
         gbk_ = k_head + (int64_t)t0k_ * p.hkv * D;                                       \
-        k_full_ = t0k_ + kBN <= p.n_keys;   /* wave-uniform */                           \
+        k_full_ = t0k_ + kBN <= n_keys_job;   /* wave-uniform */                         \
         gbv_ = v_head + min((J) + 2, n_iter - 1) * kBN;                                  \
     }
 #define PKV_DMA_PAIR(I, SDK, SDV)                                                        \
@@ -495,9 +503,37 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         __syncthreads();
         if (tid == 0) {
             const int marked = (s_red[0] | s_red[1] | s_red[2] | s_red[3]) != 0;
-            p.flags[tile * p.hkv + g] = marked;
-            if (marked) atomicAdd(&p.flags[p.n_tiles * p.hkv], 1);   // count behind the flags
+            int* const flag = &p.flags[tile * p.hkv + g];
+            int* const count = &p.flags[p.n_tiles * p.hkv];   // behind the flags
+            if (p.dma_splits == 1) {
+                *flag = marked;
+                if (marked) atomicAdd(count, 1);
+            } else if (marked && atomicOr(flag, 1) == 0) {   // flags were cleared beforehand
+                atomicAdd(count, 1);
+            }
         }
+    }
+    if (p.dma_splits > 1) {
+        // normalised partial result of this key range; rows that see none of it leave
+        // garbage that the merge never reads
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            if (!valid[cb]) continue;
+            const int64_t colg = ((int64_t)split * p.m + row[cb]) * p.hq + head[cb];
+            const float inv = 1.f / l_tot[cb];
+            float* op = p.part_o + colg * D + 4 * hh;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    f32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = o_acc[db][cb][4 * r4 + e] * inv;
+                    *reinterpret_cast<f32x4*>(op + db * 32 + r4 * 8) = v;
+                }
+            if (hh == 0) p.part_lse[colg] = m_run[cb] * p.scale + logf(l_tot[cb]);
+        }
+        continue;
     }
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
@@ -519,12 +555,41 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
   }   // next (kv head, row tile)
 }
 
+// Merge of the key ranges of a split launch: out = sum_s w_s O_s / sum_s w_s with
+// w_s = exp(lse_s - max lse), over the ranges that begin at or below the row's limit.
+// One workgroup of D threads per (row, head); tiles marked for the exact kernel are left
+// to it.
+__global__ __launch_bounds__(D) void attn_merge_splits_kernel(AttnParams p) {
+    const int64_t col = blockIdx.x;           // row * hq + head
+    const int row = (int)(col / p.hq), head = (int)(col % p.hq);
+    if (p.flags[(row / p.bm) * p.hkv + head / p.group]) return;
+    const int limit = min(p.row_pos[row], p.n_keys - 1);
+    const int n_s = limit / p.dma_split_len + 1;   // <= dma_splits
+    const int d = threadIdx.x;
+    float mx = -INFINITY;
+    for (int sp = 0; sp < n_s; ++sp)
+        mx = fmaxf(mx, p.part_lse[((int64_t)sp * p.m + row) * p.hq + head]);
+    float acc = 0.f, wsum = 0.f;
+    for (int sp = 0; sp < n_s; ++sp) {
+        const int64_t c = ((int64_t)sp * p.m + row) * p.hq + head;
+        const float w = __expf(p.part_lse[c] - mx);
+        wsum += w;
+        acc += w * p.part_o[c * D + d];
+    }
+    p.out[col * D + d] = (bf16_t)(acc / wsum);
+    if (p.lse && d == 0) p.lse[col] = mx + logf(wsum);
+}
+
 }  // namespace
 
 pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
     // every workgroup reports through p.flags; the operands must all be there
     if (!p.q || !p.k || !p.vt || !p.row_pos || !p.out || !p.flags || !p.queue)
         return PKV_ERR_NULL;
+    if (p.dma_splits < 1 || p.dma_split_len < kBN || p.dma_split_len % kBN ||
+        (int64_t)p.dma_splits * p.dma_split_len < p.n_keys)
+        return PKV_ERR_SHAPE;
+    if (p.dma_splits > 1 && (!p.part_o || !p.part_lse)) return PKV_ERR_WORKSPACE;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dma128_kernel),
@@ -543,9 +608,13 @@ pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
         n_cu = v;
     }
     // one workgroup per CU (its LDS admits no second one), or per tile if there are fewer
-    const int64_t grid = std::min<int64_t>((int64_t)p.n_tiles * p.hkv, n_cu);
+    const int64_t grid = std::min<int64_t>((int64_t)p.n_tiles * p.dma_splits * p.hkv, n_cu);
     hipLaunchKernelGGL(attn_dma128_kernel, dim3((unsigned)grid), dim3(kAttnThreads),
                        kLdsBytes, st, p);
+    if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
+    if (p.dma_splits > 1)
+        hipLaunchKernelGGL(attn_merge_splits_kernel, dim3((unsigned)((int64_t)p.m * p.hq)),
+                           dim3(D), 0, st, p);
     return launch_status();
 }
 

@@ -345,6 +345,41 @@ def test_sparse_row_attn_more_row_tiles_than_workgroups(gpu_device, hq, hkv, m, 
     assert torch.equal(out, out2) and torch.equal(lse, lse2)
 
 
+@pytest.mark.parametrize("hq,hkv,m,n_keys,query_rows", [
+    (32, 8, 128, 8192 + 128, True),      # Stage I: the query rows alone, 16 (head, tile) pairs
+    (32, 8, 200, 8300, False),           # rows anywhere: some see only the first key range
+    (8, 2, 500, 5000, False), (40, 8, 70, 3333, False)])
+def test_sparse_row_attn_few_rows_split_over_keys(gpu_device, hq, hkv, m, n_keys, query_rows):
+    """Fewer (kv head, row tile) pairs than CUs: the keys of a tile are cut into ranges
+    that run as separate jobs and are merged (rows that end inside a range, rows that
+    never reach a range, a ragged last range)."""
+    dtype, d = "bf16", 128
+    cfg = lcfg(dtype, hq, hkv, d)
+    g = np.random.default_rng(51)
+    q = rnd(52, (m, hq, d), dtype, 1.2)
+    kc, vc = rnd(53, (n_keys, hkv, d), dtype), rnd(54, (n_keys, hkv, d), dtype)
+    if query_rows:
+        pos = np.arange(n_keys - m, n_keys, dtype=np.int32)
+    else:
+        pos = np.sort(g.integers(0, n_keys, m)).astype(np.int32)
+        pos[0], pos[1], pos[-1] = 0, 1023, n_keys - 1
+    want, want_lse = O.sparse_row_attn(q.astype(np.float64), kc.astype(np.float64),
+                                       vc.astype(np.float64), pos, dtype=dtype)
+    out = torch.empty((m, hq, d), dtype=torch.bfloat16, device=gpu_device)
+    lse = torch.empty((m, hq), dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, m), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    ws.fill_(0xff)
+    args = (dev(q, dtype, gpu_device), dev(kc, dtype, gpu_device), dev(vc, dtype, gpu_device),
+            torch.from_numpy(pos).to(gpu_device))
+    api.pkv_sparse_row_attn(cfg, *args, out, lse, ws=ws)
+    assert rel_err(host(out), want) <= TOL[dtype]
+    assert np.abs(host(lse) - want_lse).max() <= 4e-3
+    out2 = torch.empty_like(out)
+    api.pkv_sparse_row_attn(cfg, *args, out2, None, ws=ws)
+    assert torch.equal(out, out2)
+
+
 def test_sparse_row_attn_closed_forms(gpu_device):
     dtype, hq, hkv, d, n_keys = "bf16", 8, 2, 128, 500
     cfg = lcfg(dtype, hq, hkv, d)
