@@ -9,7 +9,8 @@
 // Up to 64 scores per lane (n <= 65536) the keys live in registers, each lane
 // owning a contiguous run of indices (topk_bisect_kernel):
 //   1. the key tau of the k-th largest score is built bit by bit from the top:
-//      32 rounds of "how many keys are >= candidate", each a compare-and-count
+//      up to 32 rounds of "how many keys are >= candidate" (it stops at the round
+//      that leaves exactly k keys), each a compare-and-count
 //      over the lane's registers, a DPP row reduction and one barrier - no
 //      atomics, so the skewed digit distribution of real scores (all in two or
 //      three binades) costs nothing;
@@ -218,6 +219,10 @@ __global__ __launch_bounds__(kThreads) void topk_bisect_kernel(
         uint32_t cnt;
         PKV_BLOCK_COUNT(key[j] >= cand, cnt)
         if (cnt >= (uint32_t)k) tau = cand;
+        // exactly k keys at or above the candidate: they are the selection, the lower bits
+        // of the k-th key do not matter (block-uniform; with distinct scores this happens
+        // at the highest bit in which the k-th and the (k+1)-th key differ)
+        if (cnt == (uint32_t)k) break;
     }
     uint32_t n_gt;
     PKV_BLOCK_COUNT(key[j] > tau, n_gt)
