@@ -380,6 +380,37 @@ def test_sparse_row_attn_few_rows_split_over_keys(gpu_device, hq, hkv, m, n_keys
     assert torch.equal(out, out2)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_sparse_row_attn_random_shapes(gpu_device, seed):
+    """Seeded random geometry, row count, cache length and row limits (head_dim 128,
+    bf16): whatever tiling, key ranges and claim order the launcher picks, the rows match."""
+    g = np.random.default_rng(1000 + seed)
+    hq, hkv = [(32, 8), (8, 8), (16, 2), (12, 4), (40, 8), (4, 1), (64, 8)][seed % 7]
+    m = int(g.integers(1, 900))
+    n_keys = int(g.integers(1, 9000))
+    dtype, d = "bf16", 128
+    cfg = lcfg(dtype, hq, hkv, d)
+    q = rnd(2000 + seed, (m, hq, d), dtype, 1.1)
+    kc, vc = rnd(3000 + seed, (n_keys, hkv, d), dtype), rnd(4000 + seed, (n_keys, hkv, d), dtype)
+    pos = g.integers(0, n_keys, m).astype(np.int32)
+    if seed % 3 == 0:
+        pos = np.sort(pos)
+    if seed % 4 == 1:
+        pos[:] = n_keys - 1                      # every row sees the whole cache
+    want, want_lse = O.sparse_row_attn(q.astype(np.float64), kc.astype(np.float64),
+                                       vc.astype(np.float64), pos, dtype=dtype)
+    out = torch.empty((m, hq, d), dtype=torch.bfloat16, device=gpu_device)
+    lse = torch.empty((m, hq), dtype=torch.float32, device=gpu_device)
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, m), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    ws.fill_(0x5a)
+    api.pkv_sparse_row_attn(cfg, dev(q, dtype, gpu_device), dev(kc, dtype, gpu_device),
+                            dev(vc, dtype, gpu_device), torch.from_numpy(pos).to(gpu_device),
+                            out, lse, ws=ws)
+    assert rel_err(host(out), want) <= TOL[dtype], (hq, hkv, m, n_keys)
+    assert np.abs(host(lse) - want_lse).max() <= 4e-3, (hq, hkv, m, n_keys)
+
+
 def test_sparse_row_attn_closed_forms(gpu_device):
     dtype, hq, hkv, d, n_keys = "bf16", 8, 2, 128, 500
     cfg = lcfg(dtype, hq, hkv, d)
