@@ -28,6 +28,8 @@
 // 16 tiles) cannot fill 256 CUs with tiles alone, so its contraction is split: every
 // split writes fp32 partial tiles, and a second small kernel adds them in a fixed
 // order, rotates and rounds (deterministic: no atomics).
+#include <atomic>
+
 #include "proj_common.h"
 
 namespace pkv {
@@ -779,8 +781,8 @@ namespace {
 
 template <int MODE, bool EXTRA = false>
 pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set twice at worst: the calls are idempotent
+    if (!configured.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(proj_dma_kernel<MODE, EXTRA>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess ||
@@ -788,7 +790,7 @@ pkv_status launch_tiles(const ProjParams& p, hipStream_t st) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kSlabLdsBytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     const int n_tok_tiles = (int)ceil_div(p.m, T);
     const int64_t n_tiles = (int64_t)n_tok_tiles * p.tile_begin[3];

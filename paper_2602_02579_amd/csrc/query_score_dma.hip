@@ -24,6 +24,8 @@
 // tiles ahead; layout and 16-byte-chunk XOR swizzle are those of the attention
 // kernel.  One softmax step (two scores) follows every MFMA; the operands of the
 // next tile are re-read from LDS in the same rhythm.
+#include <atomic>
+
 #include "score_common.h"
 
 namespace pkv {
@@ -397,8 +399,8 @@ bool score_dma128_supported(const pkv_layer_cfg& cfg, int64_t n_ctx, int64_t nq)
 }
 
 pkv_status launch_score_dma128(int pass, const ScoreParams& p, hipStream_t st) {
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set twice at worst: the calls are idempotent
+    if (!configured.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_dma128_kernel<1>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess ||
@@ -406,7 +408,7 @@ pkv_status launch_score_dma128(int pass, const ScoreParams& p, hipStream_t st) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     if (!p.q || !p.k || (pass == 1 ? !p.part_ml : (!p.lse2 || !p.part_score)))
         return PKV_ERR_NULL;

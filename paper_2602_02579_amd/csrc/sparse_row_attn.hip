@@ -5,6 +5,7 @@
 //
 //   out[i,h] = sum_{t <= row_pos[i]} softmax_t(q[i,h] . K[t,g(h)] * scale) V[t,g(h)]
 #include <algorithm>
+#include <atomic>
 
 #include "attn_common.h"
 
@@ -495,14 +496,14 @@ size_t attn_partial_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m) {
 
 template <int D, bool kPV>
 pkv_status launch_attn_mfma(const AttnParams& p, hipStream_t st) {
-    static bool configured = false;  // per process; the attribute is per function
+    static std::atomic<bool> configured{false};   // set twice at worst: the calls are idempotent  // per process; the attribute is per function
     auto kern = attn_mfma_kernel<D, kPV>;
-    if (!configured) {
+    if (!configured.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)AttnLds<D>::bytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     int64_t grid = (int64_t)p.n_tiles * p.n_splits * p.hkv;
     if (p.flags && grid > 256) grid = 256;   // repair pass: one resident workgroup per CU

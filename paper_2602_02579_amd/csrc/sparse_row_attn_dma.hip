@@ -28,6 +28,7 @@
 //   PKV_ACC): no maximum, no rescaling and no branch in the hot loop; tiles whose
 //   probabilities leave the safe range are marked and redone by the exact kernel.
 #include <algorithm>
+#include <atomic>
 
 #include "attn_common.h"
 
@@ -590,15 +591,16 @@ pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
         (int64_t)p.dma_splits * p.dma_split_len < p.n_keys)
         return PKV_ERR_SHAPE;
     if (p.dma_splits > 1 && (!p.part_o || !p.part_lse)) return PKV_ERR_WORKSPACE;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured{false};   // set twice at worst: the calls are idempotent
+    if (!configured.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_dma128_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
-    static int n_cu = 0;   // per process; the devices of one machine are alike
+    static std::atomic<int> n_cu_cached{0};   // per process; the devices of one machine are alike
+    int n_cu = n_cu_cached.load(std::memory_order_relaxed);
     if (n_cu == 0) {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
@@ -606,6 +608,7 @@ pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
             v <= 0)
             return PKV_ERR_LAUNCH;
         n_cu = v;
+        n_cu_cached.store(v, std::memory_order_relaxed);
     }
     // one workgroup per CU (its LDS admits no second one), or per tile if there are fewer
     const int64_t grid = std::min<int64_t>((int64_t)p.n_tiles * p.dma_splits * p.hkv, n_cu);
