@@ -379,7 +379,9 @@ ScorePlan plan_score_dma128(const pkv_layer_cfg& cfg, int64_t n_ctx, int64_t nq)
     const int group = cfg.n_q_heads / cfg.n_kv_heads;
     ScorePlan sp;
     sp.n_cblk = (int)ceil_div(nq * group, 256);
-    int64_t want = ceil_div(256, (int64_t)sp.n_cblk * cfg.n_kv_heads);
+    // as many key splits as keep the launch within one round of a 256-CU part (a 257th
+    // workgroup would double the time of the launch)
+    int64_t want = 256 / ((int64_t)sp.n_cblk * cfg.n_kv_heads);
     const int64_t max_splits = ceil_div(n_ctx, 4 * kTile);
     if (want > max_splits) want = max_splits;
     if (want < 1) want = 1;
