@@ -464,18 +464,23 @@ void attn_plan_splits(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m, int* 
     *n_splits = 1;
     *split_len = (int)pad64(n_keys);
     if (cfg.head_dim != 128 || jobs >= 256 || jobs <= 0) return;
-    // Time of the launch in units of one full-length job: rounds of a 256-CU part over the
-    // ranges, each range 1/sp long, with 3 % charged per extra range for the extra
-    // prologues and the merge.  The row limits are on the device, so two layouts are
-    // weighed equally: every tile full length (jobs * sp ranges, e.g. query rows only) and
-    // limits spread evenly over the keys (about jobs * (sp + 1) / 2 ranges that hold keys).
+    // Estimated time of the launch in microseconds for sp ranges per tile: rounds of a
+    // 256-CU part over the ranges (1.4 us per 64-key step, a range 1/sp of the keys),
+    // plus what every extra range costs - its prologue on the CUs that run it (5 us) and
+    // its share of the merge, which writes and reads m * hq * D fp32 per range at about
+    // 5 TB/s.  The row limits are on the device, so two layouts are weighed equally: every
+    // tile full length (jobs * sp ranges, e.g. query rows only) and limits spread evenly
+    // over the keys (about jobs * (sp + 1) / 2 ranges that hold keys).
     const int64_t most = std::min<int64_t>(16, n_keys / 1024);
+    const double t_full = 1.4 * (double)ceil_div(n_keys, 64);
+    const double per_range = 5.0 * (double)jobs / 256.0 +
+                             2.0 * (double)m * cfg.n_q_heads * cfg.head_dim * 4.0 / 5.0e6;
     int64_t want = 1;
     double best = 1e30;
     for (int64_t sp = 1; sp <= most; ++sp) {
         const double rounds = 0.5 * (double)(ceil_div(jobs * sp, 256) +
                                              ceil_div(jobs * (sp + 1) / 2, 256));
-        const double cost = rounds / sp * (1.0 + 0.03 * (sp - 1));
+        const double cost = rounds / sp * t_full + (sp > 1 ? sp * per_range : 0.0);
         if (cost < best - 1e-9) {
             best = cost;
             want = sp;
