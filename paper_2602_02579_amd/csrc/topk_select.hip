@@ -274,6 +274,18 @@ pkv_status launch_topk_select(const float* score, int64_t n, int64_t k,
     if (n == 0 || k == 0) return PKV_OK;
     // the register kernels read 16 bytes at a time
     const bool aligned = (reinterpret_cast<uintptr_t>(score) & 15) == 0;
+    // a round costs one vector compare-and-count per register key, so short vectors take
+    // the instantiation with the fewest keys per lane that holds them
+    if (aligned && n <= 8 * kThreads) {
+        hipLaunchKernelGGL(topk_bisect_kernel<8>, dim3(1), dim3(kThreads), 0, st, score,
+                           (int)n, (int)k, idx_out);
+        return launch_status();
+    }
+    if (aligned && n <= 16 * kThreads) {
+        hipLaunchKernelGGL(topk_bisect_kernel<16>, dim3(1), dim3(kThreads), 0, st, score,
+                           (int)n, (int)k, idx_out);
+        return launch_status();
+    }
     if (aligned && n <= 32 * kThreads) {
         hipLaunchKernelGGL(topk_bisect_kernel<32>, dim3(1), dim3(kThreads), 0, st, score,
                            (int)n, (int)k, idx_out);

@@ -132,7 +132,8 @@ def run_topk(score_np, k, device):
 @pytest.mark.parametrize("n,k", [(1, 1), (63, 10), (64, 64), (1000, 0), (1000, 1000),
                                  (1024, 204), (32768, 6553), (131072, 26214),
                                  (100003, 99999), (65, 1), (50000, 12345), (65536, 100),
-                                 (32769, 32768), (40001, 1)])
+                                 (32769, 32768), (40001, 1), (8192, 1638), (8193, 8000),
+                                 (16384, 3277), (12001, 7), (16385, 16000)])
 def test_topk_matches_oracle(gpu_device, n, k):
     s = np.random.default_rng(n + k).random(n).astype(np.float32) / n
     assert np.array_equal(run_topk(s, k, gpu_device), O.topk_select(s, k))
