@@ -429,11 +429,12 @@ def test_sparse_row_attn_closed_forms(gpu_device):
         assert np.abs(got[:, h] - vc[0, h // 4]).max() <= 2e-2 * np.abs(vc[0]).max()
 
 
-def test_sparse_row_attn_scores_far_above_the_first_keys(gpu_device):
+@pytest.mark.parametrize("n_keys", [700, 3000])   # 3000: the keys of a tile run as two ranges
+def test_sparse_row_attn_scores_far_above_the_first_keys(gpu_device, n_keys):
     """Late keys whose scores exceed everything among a row's first 32 keys by
     hundreds of nats: the fixed-reference fast path of the head_dim-128 kernel
     cannot represent them and must hand the tile to the exact kernel."""
-    dtype, hq, hkv, d, n_keys, m = "bf16", 8, 2, 128, 700, 150
+    dtype, hq, hkv, d, m = "bf16", 8, 2, 128, 150
     cfg = lcfg(dtype, hq, hkv, d)
     g = np.random.default_rng(31)
     q = rnd(32, (m, hq, d), dtype, 1.0)
