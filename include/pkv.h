@@ -37,7 +37,9 @@
  *   i + D/2 and turned by position * rope_theta^(-2i/D); no frequency
  *   scaling.
  * Streams: `stream` is a hipStream_t passed as void* (NULL = the null
- *   stream).  Calls enqueue work and return without synchronising.
+ *   stream).  Calls enqueue kernels on it and return without synchronising;
+ *   nothing else is enqueued (no memset or copy nodes), so a sequence of
+ *   calls can be recorded into a HIP graph and replayed.
  * Errors: arguments that the host can check (null pointers, non-positive or
  *   inconsistent sizes, unsupported dtype or head_dim, workspace too small)
  *   give an error code and enqueue nothing.  A failed launch gives

@@ -90,6 +90,37 @@ def test_fused_cache_update_gives_the_same_bits(gpu_device):
     assert torch.equal(a.out, b.out) and torch.equal(a.q, b.q)
 
 
+def test_whole_path_replays_from_a_captured_graph(gpu_device):
+    """The calls only enqueue kernels on the caller's stream (no allocation, no clearing by
+    the runtime, no synchronisation), so a pass can be captured into a graph.  Replays, with
+    eager passes and synchronisations between them, give the bits of the eager pass."""
+    cfg = synth.CONFIGS[2]
+    layers, _ = workload.build(cfg)
+    sr, dl = run_gpu(cfg, layers, gpu_device)
+    ref = [t.clone() for t in (sr.out, sr.lse, sr.rows, dl[0]["k_cache"], dl[0]["v_cache"])]
+    side = torch.cuda.Stream()                      # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sr.run(dl)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sr.run(dl)
+    for _ in range(3):
+        for t in (sr.out, sr.lse, dl[0]["k_cache"]):   # everything a pass writes in full
+            t.zero_()
+        sr.rows[:sr.k].zero_()                         # (the value cache also holds inputs)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (sr.out, sr.lse, sr.rows, dl[0]["k_cache"], dl[0]["v_cache"])
+        assert all(torch.equal(a, b) for a, b in zip(got, ref))
+        sr.run(dl)                                  # eager work between the replays
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(got, ref))
+
+
 def test_ratio_endpoints_on_gpu(gpu_device):
     """ratio 0: plain concatenation (only query rows computed); ratio 1: every
     row recomputed, equal to the oracle's full-prefill result."""
