@@ -36,7 +36,7 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # HBM bytes per pkv_sparse_row_attn launch (V^T pre-pass + main kernel), from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/hot_path_cfg3_hbm_traffic.txt
 # (counters cannot be read from inside this process; the figure is for that workload only)
-MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 2.163e9}
+MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 1.969e9}
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
