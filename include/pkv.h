@@ -54,7 +54,11 @@
  *   pkv_swiglu_rows fall back to narrower accesses) or refuses
  *   (pkv_rmsnorm_rows, pkv_gather_rows).
  * Supported shapes: head_dim even, a multiple of 16 and <= 256;
- *   n_q_heads a multiple of n_kv_heads; hidden a multiple of 8.
+ *   n_q_heads a multiple of n_kv_heads; hidden a multiple of 8.  Token counts
+ *   up to 2^30.  pkv_sparse_row_attn (bf16) and pkv_query_score further need
+ *   head_dim * (n_keys rounded up to 64) * 2 < 2^32 and rows * n_q_heads
+ *   (query tokens * n_q_heads) < 2^31; beyond that they return
+ *   PKV_ERR_UNSUPPORTED.
  */
 #ifndef PKV_H
 #define PKV_H

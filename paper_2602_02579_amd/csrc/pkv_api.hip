@@ -3,6 +3,7 @@
 #include "pkv_common.h"
 
 #include <cmath>
+#include <cstdint>
 
 using namespace pkv;
 
@@ -53,6 +54,8 @@ pkv_status pkv_query_score(const pkv_layer_cfg* cfg, const void* q, const void* 
     pkv_status st = check_cfg(cfg);
     if (st != PKV_OK) return st;
     if (nq <= 0 || n_ctx <= 0 || n_ctx > kMaxTokens || nq > (1 << 20)) return PKV_ERR_SHAPE;
+    // the kernels count (query token, head) columns in 32-bit integers
+    if (nq * (int64_t)cfg->n_q_heads > INT32_MAX) return PKV_ERR_UNSUPPORTED;
     if (!q || !k || !score) return PKV_ERR_NULL;
     if (!std::isfinite(softmax_scale) || softmax_scale < 0.f) return PKV_ERR_SHAPE;
     const size_t need = align256(query_score_ws_bytes(*cfg, n_ctx, nq));
@@ -153,6 +156,12 @@ pkv_status pkv_sparse_row_attn(const pkv_layer_cfg* cfg, const void* q,
     pkv_status st = check_cfg(cfg);
     if (st != PKV_OK) return st;
     if (m < 0 || m > kMaxTokens || n_keys <= 0 || n_keys > kMaxTokens) return PKV_ERR_SHAPE;
+    // byte offsets inside one kv head's K rows and transposed V rows are 32-bit in the
+    // matrix-core kernels: head_dim * (keys rounded up to 64) * 2 bytes must fit
+    if (cfg->dtype == PKV_BF16 &&
+        (int64_t)cfg->head_dim * ((n_keys + 63) / 64 * 64) * 2 >= ((int64_t)1 << 32))
+        return PKV_ERR_UNSUPPORTED;
+    if (m * (int64_t)cfg->n_q_heads > INT32_MAX) return PKV_ERR_UNSUPPORTED;
     if (m == 0) return PKV_OK;
     if (!q || !k_cache || !v_cache || !row_pos || !out) return PKV_ERR_NULL;
     if (!std::isfinite(softmax_scale) || softmax_scale < 0.f) return PKV_ERR_SHAPE;

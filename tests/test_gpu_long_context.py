@@ -2,14 +2,17 @@
 N = 131072, Llama-3-8B layer geometry, bf16): the calls whose loops and offsets grow
 with the context, each against the CPU oracle.  The oracle is evaluated in full for
 the restore, the score and the selection, and on a seeded sample of rows for the
-attention (a row costs 32 x 131k x 128 fp64 multiply-adds)."""
+attention (a row costs 32 x 131k x 128 fp64 multiply-adds).  The last test runs the
+whole path of that workload (26470 recomputed rows) in the benchmark's launch
+configuration."""
 
 import numpy as np
 import pytest
 import torch
 
 from oracle import pkv_oracle as O
-from paper_2602_02579_amd import api, synth
+from paper_2602_02579_amd import api, pipeline, synth
+from tests import workload
 
 pytestmark = pytest.mark.gpu
 
@@ -85,3 +88,56 @@ def test_restore_score_and_selection_at_131k(gpu_device):
     idx = torch.empty(k_sel, dtype=torch.int32, device=gpu_device)
     api.pkv_topk_select(score, k_sel, idx)
     assert np.array_equal(idx.cpu().numpy(), O.topk_select(score.cpu().numpy(), k_sel))
+
+
+def test_whole_path_at_131k_with_26470_recomputed_rows(gpu_device):
+    """cfg 5: 256 x 512 context, 256 query tokens, ratio 0.2, planted and margin
+    repaired.  Score and selection in full and bit-exact; K/V of all 26470 recomputed
+    rows and the untouched cache rows; Q, attention output and log-sum-exp on the first
+    and last row of every 64-row tile of the attention launch plus a seeded sample."""
+    cfg = synth.CONFIGS[5]
+    layers, info = workload.build(cfg)
+    dev_layers = [pipeline.upload_layer(cfg, layers[0], gpu_device)]
+    sr = pipeline.SelectiveRecompute(cfg, gpu_device)
+    sr.run(dev_layers)
+    torch.cuda.synchronize()
+    n, qn, k = cfg.n_ctx, cfg.n_query, info["k"]
+    assert (k, sr.m) == (26214, 26470)
+    got_score = host(sr.score)
+    assert abs(got_score.sum() - 1.0) < 1e-4
+    assert np.abs(got_score - info["score"]).max() / info["score"].max() <= 1e-2
+    sel = O.topk_select(info["score"], k)
+    assert np.array_equal(sr.rows[:k].cpu().numpy(), sel)
+    assert np.isin(info["relevant"], sel).all()
+
+    L = {name: v.astype(np.float64) for name, v in layers[0].items()}
+    geo = workload.geometry(cfg)
+    rows = np.concatenate([sel, np.arange(n, n + qn)])
+    q, k_new, v_new = O.project_qkv_rows(L["hidden"], rows, rows, L["wq"], L["wk"], L["wv"],
+                                         dtype="bf16", **geo)
+    del L["hidden"]
+    k_cache = np.zeros((n + qn, HKV, D))
+    v_cache = np.zeros_like(k_cache)
+    k_cache[:n] = O.rope_restore(L["k_nope"], np.arange(n), cfg.theta, "bf16")
+    v_cache[:n] = L["v"]
+    k_cache, v_cache = O.scatter_kv(k_cache, v_cache, k_new, v_new, rows)
+    kc, vc = host(dev_layers[0]["k_cache"]), host(dev_layers[0]["v_cache"])
+    rest = np.setdiff1d(np.arange(n), sel)
+    assert np.abs(kc[rows] - k_new).max() / np.abs(k_new).max() <= 2e-2
+    assert np.abs(vc[rows] - v_new).max() / np.abs(v_new).max() <= 2e-2
+    assert np.array_equal(vc[rest], v_cache[rest])
+    assert np.abs(kc[rest] - k_cache[rest]).max() / np.abs(k_cache).max() <= 2e-2
+
+    m = len(rows)
+    first = np.arange(0, m, 64)
+    g = np.random.default_rng(55)
+    pick = np.unique(np.concatenate([first, np.minimum(first + 63, m - 1),
+                                     g.choice(m, 32, replace=False)]))
+    got_q, got_out, got_lse = host(sr.q)[pick], host(sr.out)[pick], host(sr.lse)[pick]
+    assert np.abs(got_q - q[pick]).max() / np.abs(q[pick]).max() <= 2e-2
+    for a in range(0, len(pick), 128):          # bounded [rows, keys] temporaries
+        sl = slice(a, a + 128)
+        want, want_lse = O.sparse_row_attn(q[pick[sl]], k_cache, v_cache, rows[pick[sl]],
+                                           dtype="bf16")
+        assert np.abs(got_out[sl] - want).max() / np.abs(want).max() <= 2e-2
+        assert np.abs(got_lse[sl] - want_lse).max() <= 4e-3

@@ -66,6 +66,20 @@ def test_argument_errors_are_reported_without_a_gpu():
                                    4, 10, 0.0, None, 0, None) == 1
     c2 = api.LayerCfg(32, 8, 72, 4096, 5e5, "bf16")._c()
     assert lib.pkv_rope_restore(ctypes.byref(c2), None, None, None, 0, 5, None) == 3
+    # sizes whose 32-bit byte offsets or column counts would wrap inside the kernels are
+    # refused, not run: head_dim * keys * 2 bytes >= 2**32; (rows or query tokens) * heads
+    # beyond 2**31 - 1
+    assert lib.pkv_sparse_row_attn(ctypes.byref(c), None, None, None, None, None, None,
+                                   4, 1 << 24, 0.0, None, 0, None) == 3
+    assert lib.pkv_sparse_row_attn(ctypes.byref(c), None, None, None, None, None, None,
+                                   4, (1 << 24) - 64, 0.0, None, 0, None) == 1
+    assert lib.pkv_sparse_row_attn(ctypes.byref(c), None, None, None, None, None, None,
+                                   1 << 27, 1024, 0.0, None, 0, None) == 3
+    wide = api.LayerCfg(4096, 8, 128, 4096, 5e5, "bf16")._c()
+    assert lib.pkv_query_score(ctypes.byref(wide), None, None, None, 1 << 20, 1024, 0.0, 0,
+                               None, 0, None) == 3
+    assert lib.pkv_query_score(ctypes.byref(wide), None, None, None, 1 << 10, 1024, 0.0, 0,
+                               None, 0, None) == 1
 
 
 def test_glue_and_variant_entry_points_check_their_arguments_on_the_host():

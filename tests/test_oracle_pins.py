@@ -60,10 +60,28 @@ def test_bf16_rounding_closed_forms():
         assert got == want, (x, got, want)
 
 
-def test_f32_rounding_is_numpy_cast():
+def test_f32_rounding_closed_forms():
+    """binary32 has 24 significant bits: ties go to the even neighbour, the slightest
+    excess over a tie rounds up, overflow gives inf, the subnormal quantum is 2**-149."""
+    r = lambda v: float(O.round_to_storage(np.array([v]), "f32")[0])  # noqa: E731
+    assert r(1.0 + 2.0 ** -24) == 1.0                          # tie, even mantissa below
+    assert r(1.0 + 2.0 ** -24 + 2.0 ** -40) == 1.0 + 2.0 ** -23
+    assert r(1.0 + 3 * 2.0 ** -24) == 1.0 + 2.0 ** -22         # tie, even mantissa above
+    assert r(1.0 + 2.0 ** -23) == 1.0 + 2.0 ** -23             # representable: unchanged
+    assert r(-(1.0 + 2.0 ** -24 + 2.0 ** -40)) == -(1.0 + 2.0 ** -23)
+    big = (2.0 - 2.0 ** -24) * 2.0 ** 127                      # halfway to 2**128
+    assert r(big) == np.inf and r(-big) == -np.inf
+    assert r((2.0 - 2.0 ** -23) * 2.0 ** 127) == (2.0 - 2.0 ** -23) * 2.0 ** 127
+    assert r(2.0 ** -150) == 0.0                               # tie between 0 and 2**-149
+    assert r(2.0 ** -150 + 2.0 ** -170) == 2.0 ** -149
+    assert r(3 * 2.0 ** -150) == 2.0 ** -148                   # tie, even multiple
+    # every result is a binary32 value: it survives a trip through 4-byte packing
+    import struct
     x = rng(1).standard_normal(1000) * 1e3
-    assert np.array_equal(O.round_to_storage(x, "f32"),
-                          x.astype(np.float32).astype(np.float64))
+    y = O.round_to_storage(x, "f32")
+    back = np.array([struct.unpack("<f", struct.pack("<f", v))[0] for v in y])
+    assert np.array_equal(back, y)
+    assert np.all(np.abs(y - x) <= np.abs(x) * 2.0 ** -24)
 
 
 # ---------------------------------------------------------------- RoPE
@@ -201,12 +219,22 @@ def test_score_scale_argument():
 
 
 def test_fuse_score_is_a_running_fp32_sum():
-    a = rng(10).random(100) / 100
-    s = O.fuse_score(np.zeros(100), a)
-    assert np.array_equal(s, a.astype(np.float32).astype(np.float64))
-    s2 = O.fuse_score(s, a)
-    want = (s.astype(np.float32).astype(np.float64) + a).astype(np.float32)
-    assert np.array_equal(s2, want.astype(np.float64))
+    """The fused score is rounded to binary32 after every layer: closed forms that an
+    unrounded (or once-rounded) sum would not give."""
+    one = np.array([1.0])
+    half_ulp = np.array([2.0 ** -24])
+    assert O.fuse_score(one, half_ulp)[0] == 1.0                       # tie to even
+    assert O.fuse_score(one, half_ulp + 2.0 ** -40)[0] == 1.0 + 2.0 ** -23
+    s = one
+    for _ in range(4):                       # four layers of half an ulp each
+        s = O.fuse_score(s, half_ulp)
+    assert s[0] == 1.0                       # the exact sum would be 1 + 2**-22
+    assert O.fuse_score(np.zeros(1), np.array([0.1]))[0] == 13421773 * 2.0 ** -27
+    # order matters as stated (layer order): small terms first survive
+    s = np.zeros(1)
+    for v in (2.0 ** -24, 2.0 ** -24, 1.0):
+        s = O.fuse_score(s, np.array([v]))
+    assert s[0] == 1.0 + 2.0 ** -23
 
 
 # ---------------------------------------------------------------- top-k
