@@ -274,6 +274,59 @@ pkv_status pkv_sparse_row_attn(const pkv_layer_cfg* cfg,
                                void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Fused variants for the first stage (paper: Sec. 4.2 - the user query is run through
+ * the model against the imprecise cache, and its attention to the context is the value
+ * function; Algorithm 1, first stage).  The query rows' attention pass and the score
+ * form the same exponentials of the same Q K^T; these two calls let the attention emit
+ * the normaliser the score needs, so that the score reads the keys once, not twice.
+ *
+ * pkv_sparse_row_attn_ctx_lse: pkv_sparse_row_attn that also writes
+ *   lse_ctx_out[i, h] = log sum_{t < n_ctx, t <= row_pos[i]} exp(q[i,h] . k[t,g(h)] * scale),
+ * the log-sum-exp over the CONTEXT keys alone (the first n_ctx rows of the cache; the
+ * softmax of Algorithm 1's value function runs over exactly those).  out and lse_out
+ * (may be NULL) are those of pkv_sparse_row_attn.  Built for bf16 with head_dim 128,
+ * n_ctx a multiple of 64 and at most 32 n_ctx >= n_keys; anything else returns
+ * PKV_ERR_UNSUPPORTED (use pkv_query_score then).  It is meant for launches of few rows
+ * (the user-query rows): the keys are always processed in ranges with partial results
+ * in `ws`.  Scratch: pkv_sparse_row_attn_ctx_lse_workspace_bytes(cfg, n_keys, n_ctx, m)
+ * (0 = not supported).
+ *
+ * pkv_query_score_lse: the column sums of pkv_query_score with the normalisers given:
+ *   score[t] (+)= 1/(Hq*nq) * sum_{h, q : t <= row_pos[q]} exp(q[q,h] . k[t,g(h)] * scale
+ *                                                             - lse[q, h]),  t < n_ctx.
+ * row_pos == NULL: every query row counts for every key; with lse = lse_ctx_out of the
+ * call above this is pkv_query_score exactly (up to rounding).  row_pos != NULL ([nq],
+ * device): row q counts for the keys it sees only; with lse = lse_out of
+ * pkv_sparse_row_attn over all rows of a prompt this is the attention each key RECEIVES
+ * from the whole prompt (the global column sum that Appendix B, Tab. 3 lists as the
+ * first factor of a comparison method's criterion; used by the diagnostics only).
+ * Any dtype and geometry pkv_query_score takes.  Scratch: as pkv_query_score.
+ */
+pkv_status pkv_sparse_row_attn_ctx_lse(const pkv_layer_cfg* cfg,
+                                       const void* q,          /* [m, Hq, D] */
+                                       const void* k_cache,    /* [n_keys, Hkv, D] */
+                                       const void* v_cache,    /* [n_keys, Hkv, D] */
+                                       const int32_t* row_pos, /* [m] */
+                                       void* out,              /* [m, Hq, D] */
+                                       float* lse_out,         /* [m, Hq] or NULL */
+                                       float* lse_ctx_out,     /* [m, Hq] */
+                                       int64_t m, int64_t n_keys, int64_t n_ctx,
+                                       float softmax_scale, void* ws, size_t ws_bytes,
+                                       void* stream);
+
+size_t pkv_sparse_row_attn_ctx_lse_workspace_bytes(const pkv_layer_cfg* cfg, int64_t n_keys,
+                                                   int64_t n_ctx, int64_t m);
+
+pkv_status pkv_query_score_lse(const pkv_layer_cfg* cfg,
+                               const void* q,          /* [nq, Hq, D]     */
+                               const void* k,          /* [n_ctx, Hkv, D] */
+                               const float* lse,       /* [nq, Hq]        */
+                               const int32_t* row_pos, /* [nq] or NULL    */
+                               float* score,           /* [n_ctx]         */
+                               int64_t nq, int64_t n_ctx, float softmax_scale,
+                               int accumulate, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Scratch bytes the given call needs for a problem with `n` cache/context
  * tokens and `m` rows (query tokens for PKV_CALL_QUERY_SCORE).  Pure host
  * function; returns 0 for calls that need none and for invalid arguments.

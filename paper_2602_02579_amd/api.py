@@ -17,8 +17,10 @@ from typing import Optional
 import torch
 
 __all__ = ["LayerCfg", "PkvError", "load_library", "library_path",
-           "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
-           "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex",
+           "pkv_rope_restore", "pkv_query_score",
+           "pkv_query_score_lse", "pkv_sparse_row_attn_ctx_lse",
+           "pkv_sparse_row_attn_ctx_lse_workspace_bytes",
+           "pkv_topk_select", "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex",
            "pkv_gather_qkv_proj_scatter", "pkv_scatter_kv",
            "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
            "pkv_glue_workspace_bytes",
@@ -33,7 +35,8 @@ EXPORTED_SYMBOLS = [
     "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
     "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_gather_qkv_proj_scatter",
     "pkv_scatter_kv", "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
-    "pkv_glue_workspace_bytes",
+    "pkv_glue_workspace_bytes", "pkv_query_score_lse", "pkv_sparse_row_attn_ctx_lse",
+    "pkv_sparse_row_attn_ctx_lse_workspace_bytes",
     "pkv_workspace_bytes", "pkv_status_string", "pkv_version",
 ]
 
@@ -104,6 +107,13 @@ def load_library() -> ctypes.CDLL:
     lib.pkv_query_score.argtypes = [cfgp, vp, vp, f32p, i64, i64, ctypes.c_float,
                                     ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.pkv_topk_select.argtypes = [f32p, i64, i64, i32p, vp, ctypes.c_size_t, vp]
+    lib.pkv_query_score_lse.argtypes = [cfgp, vp, vp, f32p, i32p, f32p, i64, i64,
+                                        ctypes.c_float, ctypes.c_int, vp, ctypes.c_size_t, vp]
+    lib.pkv_sparse_row_attn_ctx_lse.argtypes = [cfgp, vp, vp, vp, i32p, vp, f32p, f32p, i64,
+                                                i64, i64, ctypes.c_float, vp,
+                                                ctypes.c_size_t, vp]
+    lib.pkv_sparse_row_attn_ctx_lse_workspace_bytes.argtypes = [cfgp, i64, i64, i64]
+    lib.pkv_sparse_row_attn_ctx_lse_workspace_bytes.restype = ctypes.c_size_t
     lib.pkv_gather_qkv_proj.argtypes = [cfgp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp,
                                         i64, vp, ctypes.c_size_t, vp]
     lib.pkv_gather_qkv_proj_ex.argtypes = [cfgp, vp, i32p, i32p, vp, vp, vp,
@@ -124,7 +134,8 @@ def load_library() -> ctypes.CDLL:
                                     ctypes.c_size_t, vp]
     lib.pkv_glue_workspace_bytes.argtypes = [i32, i64, i64, i64]
     lib.pkv_glue_workspace_bytes.restype = ctypes.c_size_t
-    for name in ("pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
+    for name in ("pkv_rope_restore", "pkv_query_score",
+                 "pkv_topk_select", "pkv_query_score_lse", "pkv_sparse_row_attn_ctx_lse",
                  "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex",
                  "pkv_gather_qkv_proj_scatter", "pkv_scatter_kv",
                  "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows",
@@ -373,6 +384,64 @@ def pkv_sparse_row_attn(cfg: LayerCfg, q: torch.Tensor, k_cache: torch.Tensor,
         _ptr(v_cache, dt, "v_cache"), _ptr(row_pos, torch.int32, "row_pos"),
         _ptr(out, dt, "out"), _ptr(lse_out, torch.float32, "lse_out"), m, n_keys,
         float(softmax_scale), wp, wb, _stream()))
+
+
+def pkv_sparse_row_attn_ctx_lse_workspace_bytes(cfg: LayerCfg, n_keys: int, n_ctx: int,
+                                                m: int) -> int:
+    """Scratch of pkv_sparse_row_attn_ctx_lse; 0 when the geometry is not supported."""
+    c = cfg._c()
+    return int(load_library().pkv_sparse_row_attn_ctx_lse_workspace_bytes(
+        ctypes.byref(c), int(n_keys), int(n_ctx), int(m)))
+
+
+def pkv_sparse_row_attn_ctx_lse(cfg: LayerCfg, q: torch.Tensor, k_cache: torch.Tensor,
+                                v_cache: torch.Tensor, row_pos: torch.Tensor,
+                                out: torch.Tensor, lse_out: Optional[torch.Tensor],
+                                lse_ctx_out: torch.Tensor, n_ctx: int,
+                                softmax_scale: float = 0.0,
+                                ws: Optional[torch.Tensor] = None) -> None:
+    m, n_keys = row_pos.shape[0], k_cache.shape[0]
+    dt = cfg.torch_dtype
+    if tuple(q.shape) != (m, cfg.n_q_heads, cfg.head_dim) or out.shape != q.shape:
+        raise ValueError("q/out must be [m, Hq, D]")
+    if tuple(k_cache.shape) != (n_keys, cfg.n_kv_heads, cfg.head_dim) or \
+            v_cache.shape != k_cache.shape:
+        raise ValueError("caches must be [n_keys, Hkv, D]")
+    for name, t in (("lse_out", lse_out), ("lse_ctx_out", lse_ctx_out)):
+        if t is not None and tuple(t.shape) != (m, cfg.n_q_heads):
+            raise ValueError(f"{name} must be [m, Hq]")
+    wp, wb = _ws(ws)
+    c = cfg._c()
+    _check("pkv_sparse_row_attn_ctx_lse", load_library().pkv_sparse_row_attn_ctx_lse(
+        ctypes.byref(c), _ptr(q, dt, "q"), _ptr(k_cache, dt, "k_cache"),
+        _ptr(v_cache, dt, "v_cache"), _ptr(row_pos, torch.int32, "row_pos"),
+        _ptr(out, dt, "out"), _ptr(lse_out, torch.float32, "lse_out"),
+        _ptr(lse_ctx_out, torch.float32, "lse_ctx_out"), m, n_keys, int(n_ctx),
+        float(softmax_scale), wp, wb, _stream()))
+
+
+def pkv_query_score_lse(cfg: LayerCfg, q: torch.Tensor, k: torch.Tensor, lse: torch.Tensor,
+                        row_pos: Optional[torch.Tensor], score: torch.Tensor,
+                        accumulate: bool = False, softmax_scale: float = 0.0,
+                        ws: Optional[torch.Tensor] = None) -> None:
+    nq, n_ctx = q.shape[0], k.shape[0]
+    if tuple(q.shape) != (nq, cfg.n_q_heads, cfg.head_dim):
+        raise ValueError("q must be [nq, Hq, D]")
+    if tuple(k.shape) != (n_ctx, cfg.n_kv_heads, cfg.head_dim):
+        raise ValueError("k must be [n_ctx, Hkv, D]")
+    if tuple(lse.shape) != (nq, cfg.n_q_heads):
+        raise ValueError("lse must be [nq, Hq]")
+    if row_pos is not None and tuple(row_pos.shape) != (nq,):
+        raise ValueError("row_pos must be [nq]")
+    if tuple(score.shape) != (n_ctx,):
+        raise ValueError("score must be [n_ctx]")
+    wp, wb = _ws(ws)
+    c = cfg._c()
+    _check("pkv_query_score_lse", load_library().pkv_query_score_lse(
+        ctypes.byref(c), _ptr(q, cfg.torch_dtype, "q"), _ptr(k, cfg.torch_dtype, "k"),
+        _ptr(lse, torch.float32, "lse"), _ptr(row_pos, torch.int32, "row_pos"),
+        _ptr(score, torch.float32, "score"), nq, n_ctx, float(softmax_scale),
+        int(bool(accumulate)), wp, wb, _stream()))
 
 
 # ---- layer glue -------------------------------------------------------------------

@@ -23,6 +23,8 @@ struct AttnParams {
     float* part_o;           // [dma_splits, m, hq, D] normalised partial outputs, and
     float* part_lse;         // [dma_splits, m, hq] their log-sum-exp (pipelined kernel with
                              // dma_splits > 1 only)
+    float* lse_ctx;          // [m, hq] or nullptr: log-sum-exp over the keys below ctx_keys
+    int ctx_keys;            // a multiple of dma_split_len (and of 64) when lse_ctx is set
     int dma_splits, dma_split_len;   // key ranges per row tile in the pipelined kernel
     int m, n_keys, n_pad, hq, hkv, group, bm, n_tiles, n_splits, split_len;
     int fixed_limit;         // >= 0: every row sees keys 0..fixed_limit

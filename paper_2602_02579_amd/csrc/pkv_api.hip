@@ -65,6 +65,23 @@ pkv_status pkv_query_score(const pkv_layer_cfg* cfg, const void* q, const void* 
                               ws, (hipStream_t)stream);
 }
 
+pkv_status pkv_query_score_lse(const pkv_layer_cfg* cfg, const void* q, const void* k,
+                               const float* lse, const int32_t* row_pos, float* score,
+                               int64_t nq, int64_t n_ctx, float softmax_scale,
+                               int accumulate, void* ws, size_t ws_bytes, void* stream) {
+    pkv_status st = check_cfg(cfg);
+    if (st != PKV_OK) return st;
+    if (nq <= 0 || n_ctx <= 0 || n_ctx > kMaxTokens || nq > kMaxTokens) return PKV_ERR_SHAPE;
+    if (nq * (int64_t)cfg->n_q_heads > INT32_MAX) return PKV_ERR_UNSUPPORTED;
+    if (!q || !k || !lse || !score) return PKV_ERR_NULL;
+    if (!std::isfinite(softmax_scale) || softmax_scale < 0.f) return PKV_ERR_SHAPE;
+    const size_t need = align256(query_score_ws_bytes(*cfg, n_ctx, nq));
+    if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
+    return launch_query_score_lse(*cfg, q, k, lse, row_pos, score, nq, n_ctx,
+                                  resolve_scale(softmax_scale, cfg->head_dim), accumulate,
+                                  ws, (hipStream_t)stream);
+}
+
 pkv_status pkv_topk_select(const float* score, int64_t n, int64_t k,
                            int32_t* idx_out, void* ws, size_t ws_bytes,
                            void* stream) {
@@ -170,6 +187,41 @@ pkv_status pkv_sparse_row_attn(const pkv_layer_cfg* cfg, const void* q,
     return launch_sparse_row_attn(*cfg, q, k_cache, v_cache, row_pos, out, lse_out, m,
                                   n_keys, resolve_scale(softmax_scale, cfg->head_dim),
                                   ws, (hipStream_t)stream);
+}
+
+pkv_status pkv_sparse_row_attn_ctx_lse(const pkv_layer_cfg* cfg, const void* q,
+                                       const void* k_cache, const void* v_cache,
+                                       const int32_t* row_pos, void* out, float* lse_out,
+                                       float* lse_ctx_out, int64_t m, int64_t n_keys,
+                                       int64_t n_ctx, float softmax_scale, void* ws,
+                                       size_t ws_bytes, void* stream) {
+    pkv_status st = check_cfg(cfg);
+    if (st != PKV_OK) return st;
+    if (m < 0 || m > kMaxTokens || n_keys <= 0 || n_keys > kMaxTokens || n_ctx <= 0 ||
+        n_ctx > n_keys)
+        return PKV_ERR_SHAPE;
+    if (cfg->dtype == PKV_BF16 &&
+        (int64_t)cfg->head_dim * ((n_keys + 63) / 64 * 64) * 2 >= ((int64_t)1 << 32))
+        return PKV_ERR_UNSUPPORTED;
+    if (m * (int64_t)cfg->n_q_heads > INT32_MAX) return PKV_ERR_UNSUPPORTED;
+    if (m == 0) return PKV_OK;
+    if (!sparse_row_attn_ctx_lse_supported(*cfg, n_keys, m, n_ctx)) return PKV_ERR_UNSUPPORTED;
+    if (!q || !k_cache || !v_cache || !row_pos || !out || !lse_ctx_out) return PKV_ERR_NULL;
+    if (!std::isfinite(softmax_scale) || softmax_scale < 0.f) return PKV_ERR_SHAPE;
+    const size_t need = align256(sparse_row_attn_ws_bytes(*cfg, n_keys, m, n_ctx));
+    if (need && (!ws || ws_bytes < need)) return PKV_ERR_WORKSPACE;
+    return launch_sparse_row_attn(*cfg, q, k_cache, v_cache, row_pos, out, lse_out, m, n_keys,
+                                  resolve_scale(softmax_scale, cfg->head_dim), ws,
+                                  (hipStream_t)stream, n_ctx, lse_ctx_out);
+}
+
+size_t pkv_sparse_row_attn_ctx_lse_workspace_bytes(const pkv_layer_cfg* cfg, int64_t n_keys,
+                                                   int64_t n_ctx, int64_t m) {
+    if (check_cfg(cfg) != PKV_OK || n_keys <= 0 || n_ctx <= 0 || m <= 0 || n_ctx > n_keys ||
+        n_keys > kMaxTokens || m > kMaxTokens)
+        return 0;
+    if (!sparse_row_attn_ctx_lse_supported(*cfg, n_keys, m, n_ctx)) return 0;
+    return align256(sparse_row_attn_ws_bytes(*cfg, n_keys, m, n_ctx));
 }
 
 pkv_status pkv_rmsnorm_rows(int32_t dtype, const void* h, const int32_t* row_idx,

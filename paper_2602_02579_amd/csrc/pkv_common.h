@@ -90,6 +90,11 @@ pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
                               int64_t n_ctx, float scale, int accumulate,
                               void* ws, hipStream_t st);
 
+pkv_status launch_query_score_lse(const pkv_layer_cfg& cfg, const void* q, const void* k,
+                                  const float* lse, const int32_t* row_pos, float* score,
+                                  int64_t nq, int64_t n_ctx, float scale, int accumulate,
+                                  void* ws, hipStream_t st);
+
 pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
                                   const int32_t* row_idx, const int32_t* row_pos,
                                   const void* wq, const void* wk, const void* wv,
@@ -98,12 +103,17 @@ pkv_status launch_gather_qkv_proj(const pkv_layer_cfg& cfg, const void* hidden,
                                   hipStream_t st);
 size_t gather_qkv_proj_ws_bytes(const pkv_layer_cfg& cfg, int64_t m);
 
-size_t sparse_row_attn_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m);
+// ctx_keys > 0 with lse_ctx_out: also the log-sum-exp over the keys below ctx_keys
+size_t sparse_row_attn_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m,
+                                int64_t ctx_keys = 0);
+bool sparse_row_attn_ctx_lse_supported(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m,
+                                       int64_t ctx_keys);
 pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
                                   const void* k_cache, const void* v_cache,
                                   const int32_t* row_pos, void* out,
                                   float* lse_out, int64_t m, int64_t n_keys,
-                                  float scale, void* ws, hipStream_t st);
+                                  float scale, void* ws, hipStream_t st,
+                                  int64_t ctx_keys = 0, float* lse_ctx_out = nullptr);
 
 // layer glue (layer_glue.hip); dtype is a pkv_dtype
 pkv_status launch_rmsnorm_rows(int dtype, const void* h, const int32_t* row_idx,

@@ -89,7 +89,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void score_colsum_generic(
     const T* __restrict__ q, const T* __restrict__ k,
     const float* __restrict__ lse, float* __restrict__ score, int nq, int n_ctx,
-    int hq, int hkv, int d, float scale, int accumulate) {
+    int hq, int hkv, int d, float scale, int accumulate,
+    const int32_t* __restrict__ row_pos = nullptr) {
     __shared__ float qs[256];
     const int t = blockIdx.x * 256 + threadIdx.x;
     float sum = 0.f;
@@ -98,7 +99,8 @@ __global__ __launch_bounds__(256) void score_colsum_generic(
         __syncthreads();
         if (threadIdx.x < d) qs[threadIdx.x] = Elem<T>::load(q + (int64_t)col * d + threadIdx.x);
         __syncthreads();
-        if (t < n_ctx) {
+        // with row limits a query row only counts for the keys it sees
+        if (t < n_ctx && (!row_pos || t <= row_pos[col / hq])) {
             const int g = (col % hq) / (hq / hkv);
             const float s = dot_row<T>(qs, k + ((int64_t)t * hkv + g) * d, d) * scale;
             sum += expf(s - lse[col]);
@@ -159,11 +161,14 @@ __global__ __launch_bounds__(256) void merge_lse_kernel(const float* __restrict_
     }
 }
 
-template <int D>
+// kCausal: row_pos[query row] is the last key that row sees; column blocks that see
+// nothing of this wave's keys are skipped, the others are masked per key.
+template <int D, bool kCausal = false>
 __global__ __launch_bounds__(256) void score_colsum_mfma(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
     const float* __restrict__ lse2, float* __restrict__ part_score, int nq, int n_ctx,
-    int hq, int hkv, int group, float scale_log2) {
+    int hq, int hkv, int group, float scale_log2,
+    const int32_t* __restrict__ row_pos = nullptr) {
     constexpr int KC = D / 16;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -191,7 +196,8 @@ __global__ __launch_bounds__(256) void score_colsum_mfma(
     // are switched off through an infinite normaliser)
     bf16x8 b[KC], bn[KC];
     float norm, norm_n;
-    auto load_cols = [&](int c0, bf16x8* dst, float* nrm) {
+    int lim = 0x7fffffff, lim_n = 0x7fffffff;   // last key the lane's column sees
+    auto load_cols = [&](int c0, bf16x8* dst, float* nrm, int* limit) {
         const int col = min(c0 + l32, ncol_g - 1);
         const int qi = col / group;
         const int h = g * group + col % group;
@@ -199,10 +205,19 @@ __global__ __launch_bounds__(256) void score_colsum_mfma(
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) dst[kc] = *reinterpret_cast<const bf16x8*>(qp + kc * 16);
         *nrm = c0 + l32 < ncol_g ? lse2[(int64_t)qi * hq + h] : INFINITY;
+        if (kCausal) *limit = c0 + l32 < ncol_g ? row_pos[qi] : -1;
     };
-    load_cols(0, b, &norm);
+    load_cols(0, b, &norm, &lim);
     for (int c0 = 0; c0 < ncol_g; c0 += 32) {
-        load_cols(min(c0 + 32, ncol_g - 1), bn, &norm_n);   // next block, in flight during the MFMAs
+        // next block, in flight during the MFMAs
+        load_cols(min(c0 + 32, ncol_g - 1), bn, &norm_n, &lim_n);
+        if (kCausal && __ballot(lim >= key0) == 0) {   // nobody here sees these keys
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) b[kc] = bn[kc];
+            norm = norm_n;
+            lim = lim_n;
+            continue;
+        }
         f32x16 s[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -216,11 +231,19 @@ __global__ __launch_bounds__(256) void score_colsum_mfma(
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[kb][r] += __builtin_amdgcn_exp2f(s[kb][r] * scale_log2 - norm);
+            for (int r = 0; r < 16; ++r) {
+                const float e = __builtin_amdgcn_exp2f(s[kb][r] * scale_log2 - norm);
+                if (kCausal) {
+                    const int key = key0 + 32 * kb + 8 * (r / 4) + 4 * hh + (r % 4);
+                    acc[kb][r] += key <= lim ? e : 0.f;
+                } else {
+                    acc[kb][r] += e;
+                }
+            }
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) b[kc] = bn[kc];
         norm = norm_n;
+        lim = lim_n;
     }
     // sum over the 32 columns held by the lanes of each half
 #pragma unroll
@@ -262,6 +285,14 @@ __global__ __launch_bounds__(256) void finish_score_kernel(const float* __restri
     }
 }
 
+// natural-log normalisers (what the attention call emits) -> the log2-domain ones the
+// column-sum kernels subtract
+__global__ __launch_bounds__(256) void lse_to_log2_kernel(const float* __restrict__ lse,
+                                                          float* __restrict__ lse2, int ncol) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < ncol) lse2[i] = lse[i] * 1.4426950408889634f;
+}
+
 bool mfma_score_supported(const pkv_layer_cfg& cfg) {
     const int group = cfg.n_q_heads / cfg.n_kv_heads;
     return cfg.dtype == PKV_BF16 && (cfg.head_dim == 64 || cfg.head_dim == 128) &&
@@ -298,16 +329,19 @@ pkv_status launch_attn_lse_partials(const pkv_layer_cfg& cfg, const void* q,
 size_t query_score_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_ctx, int64_t nq) {
     const size_t ncol = (size_t)(nq * cfg.n_q_heads);
     if (!mfma_score_supported(cfg)) return ncol * sizeof(float);
-    if (score_dma128_supported(cfg, n_ctx, nq)) {
-        const ScorePlan sp = plan_score_dma128(cfg, n_ctx, nq);
-        return align_up(ncol * sizeof(float)) +
-               align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)) +
-               align_up((size_t)sp.n_parts * n_ctx * sizeof(float));
-    }
+    // the key-blocked kernels (other geometries, and the column sums with row limits)
     const SplitPlan sp = plan_splits(cfg, n_ctx, nq);
-    return align_up(ncol * sizeof(float)) +
-           align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)) +
-           align_up((size_t)cfg.n_kv_heads * n_ctx * sizeof(float));
+    size_t need = align_up(ncol * sizeof(float)) +
+                  align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)) +
+                  align_up((size_t)cfg.n_kv_heads * n_ctx * sizeof(float));
+    if (score_dma128_supported(cfg, n_ctx, nq)) {
+        const ScorePlan dp = plan_score_dma128(cfg, n_ctx, nq);
+        const size_t dma = align_up(ncol * sizeof(float)) +
+                           align_up((size_t)dp.n_splits * ncol * 2 * sizeof(float)) +
+                           align_up((size_t)dp.n_parts * n_ctx * sizeof(float));
+        if (dma > need) need = dma;
+    }
+    return need;
 }
 
 pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
@@ -388,6 +422,72 @@ pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
                            (const float*)q, (const float*)k, lse, score, (int)nq,
                            (int)n_ctx, hq, hkv, d, scale, accumulate);
     }
+    return launch_status();
+}
+
+// Column sums with normalisers supplied by the caller (one key stream instead of two).
+// row_pos == nullptr: every query row counts for every key, the fast kernels run.
+// row_pos != nullptr: query row i counts for keys <= row_pos[i] only.
+pkv_status launch_query_score_lse(const pkv_layer_cfg& cfg, const void* q, const void* k,
+                                  const float* lse, const int32_t* row_pos, float* score,
+                                  int64_t nq, int64_t n_ctx, float scale, int accumulate,
+                                  void* ws, hipStream_t st) {
+    const int ncol = (int)(nq * cfg.n_q_heads);
+    const int hq = cfg.n_q_heads, hkv = cfg.n_kv_heads, d = cfg.head_dim;
+    const float scale_log2 = scale * 1.4426950408889634f;
+    if (!mfma_score_supported(cfg)) {
+        const unsigned kb = (unsigned)ceil_div(n_ctx, 256);
+        if (cfg.dtype == PKV_BF16)
+            hipLaunchKernelGGL(score_colsum_generic<bf16_t>, dim3(kb), dim3(256), 0, st,
+                               (const bf16_t*)q, (const bf16_t*)k, lse, score, (int)nq,
+                               (int)n_ctx, hq, hkv, d, scale, accumulate, row_pos);
+        else
+            hipLaunchKernelGGL(score_colsum_generic<float>, dim3(kb), dim3(256), 0, st,
+                               (const float*)q, (const float*)k, lse, score, (int)nq,
+                               (int)n_ctx, hq, hkv, d, scale, accumulate, row_pos);
+        return launch_status();
+    }
+    // workspace layout of launch_query_score: normalisers first, the partial column sums
+    // behind the (unused here) partial normalisers
+    unsigned char* base = (unsigned char*)ws;
+    float* lse2 = (float*)base;
+    hipLaunchKernelGGL(lse_to_log2_kernel, dim3((unsigned)ceil_div(ncol, 256)), dim3(256), 0,
+                       st, lse, lse2, ncol);
+    if (!row_pos && score_dma128_supported(cfg, n_ctx, nq)) {
+        const ScorePlan sp = plan_score_dma128(cfg, n_ctx, nq);
+        float* part_score = (float*)(base + align_up((size_t)ncol * sizeof(float)) +
+                                     align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)));
+        ScoreParams sp_ = {};
+        sp_.q = (const bf16_t*)q;
+        sp_.k = (const bf16_t*)k;
+        sp_.lse2 = lse2;
+        sp_.part_score = part_score;
+        sp_.nq = (int)nq; sp_.n_ctx = (int)n_ctx; sp_.hq = hq; sp_.hkv = hkv; sp_.group = hq / hkv;
+        sp_.n_cblk = sp.n_cblk; sp_.n_splits = sp.n_splits; sp_.split_len = sp.split_len;
+        sp_.scale_log2 = scale_log2;
+        const pkv_status stt = launch_score_dma128(2, sp_, st);
+        if (stt != PKV_OK) return stt;
+        hipLaunchKernelGGL(finish_score_kernel, dim3((unsigned)ceil_div(n_ctx, 64)),
+                           dim3(256), 0, st, part_score, score, (int)n_ctx, sp.n_parts,
+                           1.0f / (float)ncol, accumulate);
+        return launch_status();
+    }
+    const SplitPlan sp = plan_splits(cfg, n_ctx, nq);
+    float* part_score = (float*)(base + align_up((size_t)ncol * sizeof(float)) +
+                                 align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)));
+    const dim3 grid((unsigned)ceil_div(n_ctx, 256), (unsigned)hkv);
+#define PKV_COLSUM(DD, CAUSAL)                                                              \
+    hipLaunchKernelGGL((score_colsum_mfma<DD, CAUSAL>), grid, dim3(256), 0, st,             \
+                       (const bf16_t*)q, (const bf16_t*)k, lse2, part_score, (int)nq,       \
+                       (int)n_ctx, hq, hkv, hq / hkv, scale_log2, row_pos)
+    if (d == 128) {
+        if (row_pos) PKV_COLSUM(128, true); else PKV_COLSUM(128, false);
+    } else {
+        if (row_pos) PKV_COLSUM(64, true); else PKV_COLSUM(64, false);
+    }
+#undef PKV_COLSUM
+    hipLaunchKernelGGL(finish_score_kernel, dim3((unsigned)ceil_div(n_ctx, 64)), dim3(256), 0,
+                       st, part_score, score, (int)n_ctx, hkv, 1.0f / (float)ncol, accumulate);
     return launch_status();
 }
 

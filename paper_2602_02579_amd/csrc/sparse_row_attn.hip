@@ -211,6 +211,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
 
     float m_run[2] = {-INFINITY, -INFINITY};
     float l_run[2] = {0.f, 0.f};
+    // state at the context boundary (p.ctx_keys, a multiple of the key tile), for the
+    // log-sum-exp over the context keys alone; NaN marks "boundary not reached"
+    float m_ctx[2] = {0.f, 0.f}, l_ctx[2] = {-1.f, -1.f};
     f32x16 o_acc[DB][2];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -351,6 +354,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
                 }
         }
 
+        if (p.lse_ctx && t0 + kBN == p.ctx_keys) {
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                m_ctx[cb] = m_run[cb];
+                l_ctx[cb] = l_run[cb];
+            }
+        }
         if (it + 1 < n_iter) store_tile(buf ^ 1);
         __syncthreads();
     }
@@ -383,6 +393,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
             }
             if (p.lse && hh == 0)
                 p.lse[colg] = m_run[cb] * p.scale + logf(l_run[cb]);
+            if (p.lse_ctx && hh == 0)   // tiles that end below the boundary: all they saw
+                p.lse_ctx[colg] = l_ctx[cb] < 0.f ? m_run[cb] * p.scale + logf(l_run[cb])
+                                                  : m_ctx[cb] * p.scale + logf(l_ctx[cb]);
         }
     }
     __syncthreads();   // LDS and s_red are reused by the next work item
@@ -457,6 +470,16 @@ size_t attn_flag_bytes(const pkv_layer_cfg& cfg, int64_t m) {
 // 16 ranges (at least 1024 keys each, multiples of 64) so that the jobs fill the CUs of a
 // 256-CU part in as few rounds per unit of work as possible; the jobs write normalised
 // partial results that a small kernel merges.
+constexpr int kMaxCtxRanges = 32;   // ranges per tile when a boundary is forced
+
+// ctx_keys > 0: a range boundary must sit exactly at ctx_keys (a multiple of 64), because
+// the log-sum-exp over the keys below it is read off the per-range partial results.  The
+// context is cut into as many equal ranges as the time estimate wants, rounded down to a
+// divisor of its length in 64-key units; the keys behind it take further ranges of that
+// length.  Returns false when that would take more than kMaxCtxRanges ranges.
+bool attn_plan_splits_at(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m, int64_t ctx_keys,
+                         int* n_splits, int* split_len);
+
 void attn_plan_splits(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m, int* n_splits,
                       int* split_len) {
     const int bm = 256 / (cfg.n_q_heads / cfg.n_kv_heads);
@@ -491,9 +514,31 @@ void attn_plan_splits(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m, int* 
     *split_len = (int)len;
     *n_splits = (int)ceil_div(n_keys, len);
 }
-size_t attn_partial_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m) {
+bool attn_plan_splits_at(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m, int64_t ctx_keys,
+                         int* n_splits, int* split_len) {
+    int want = 1, len = 0;
+    attn_plan_splits(cfg, n_keys, m, &want, &len);
+    const int64_t units = ctx_keys / 64;
+    for (int64_t s = std::min<int64_t>(std::max(want, 1), units); s >= 1; --s) {
+        if (units % s) continue;
+        const int64_t l = ctx_keys / s;
+        const int64_t total = ceil_div(n_keys, l);
+        if (total > kMaxCtxRanges) continue;
+        *split_len = (int)l;
+        *n_splits = (int)total;
+        return true;
+    }
+    return false;
+}
+
+size_t attn_partial_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m,
+                          int64_t ctx_keys = 0) {
     int n_splits, split_len;
-    attn_plan_splits(cfg, n_keys, m, &n_splits, &split_len);
+    if (ctx_keys > 0) {
+        if (!attn_plan_splits_at(cfg, n_keys, m, ctx_keys, &n_splits, &split_len)) return 0;
+    } else {
+        attn_plan_splits(cfg, n_keys, m, &n_splits, &split_len);
+    }
     if (n_splits <= 1) return 0;
     const size_t cols = (size_t)m * cfg.n_q_heads;
     return (size_t)n_splits * cols * (cfg.head_dim + 1) * sizeof(float);
@@ -519,10 +564,19 @@ pkv_status launch_attn_mfma(const AttnParams& p, hipStream_t st) {
 
 }  // namespace
 
-size_t sparse_row_attn_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m) {
+size_t sparse_row_attn_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m,
+                                int64_t ctx_keys) {
     if (!mfma_attn_supported(cfg)) return 0;
     return attn_vt_bytes(cfg, n_keys) + attn_flag_bytes(cfg, m) +
-           attn_partial_bytes(cfg, n_keys, m);
+           attn_partial_bytes(cfg, n_keys, m, ctx_keys);
+}
+
+bool sparse_row_attn_ctx_lse_supported(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m,
+                                       int64_t ctx_keys) {
+    int a, b;
+    return mfma_attn_supported(cfg) && cfg.head_dim == 128 && ctx_keys > 0 &&
+           ctx_keys % 64 == 0 && ctx_keys <= n_keys &&
+           attn_plan_splits_at(cfg, n_keys, m, ctx_keys, &a, &b);
 }
 
 // Per-column (max, sum) partials of softmax(q k^T * scale) over keys
@@ -557,9 +611,12 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
                                   const void* k_cache, const void* v_cache,
                                   const int32_t* row_pos, void* out,
                                   float* lse_out, int64_t m, int64_t n_keys,
-                                  float scale, void* ws, hipStream_t st) {
+                                  float scale, void* ws, hipStream_t st,
+                                  int64_t ctx_keys, float* lse_ctx_out) {
     if (m == 0) return PKV_OK;
     const int d = cfg.head_dim;
+    if (lse_ctx_out && !sparse_row_attn_ctx_lse_supported(cfg, n_keys, m, ctx_keys))
+        return PKV_ERR_UNSUPPORTED;
     if (mfma_attn_supported(cfg)) {
         const int n_pad = (int)pad64(n_keys);
         bf16_t* vt = (bf16_t*)ws;
@@ -567,7 +624,10 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         const int n_flags =
             (int)ceil_div(m, 256 / (cfg.n_q_heads / cfg.n_kv_heads)) * cfg.n_kv_heads;
         int n_splits = 1, split_len = n_pad;
-        attn_plan_splits(cfg, n_keys, m, &n_splits, &split_len);
+        if (lse_ctx_out)
+            attn_plan_splits_at(cfg, n_keys, m, ctx_keys, &n_splits, &split_len);
+        else
+            attn_plan_splits(cfg, n_keys, m, &n_splits, &split_len);
         // cleared by the pre-pass: marked count + queue counters, and the marks when split
         int* zero = d == 128 ? (n_splits > 1 ? ints : ints + n_flags) : nullptr;
         const int n_zero = (n_splits > 1 ? n_flags : 0) + 1 + cfg.n_kv_heads;
@@ -603,6 +663,8 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         p.queue = p.flags + p.n_tiles * p.hkv + 1;
         p.dma_splits = n_splits;
         p.dma_split_len = split_len;
+        p.lse_ctx = lse_ctx_out;
+        p.ctx_keys = (int)ctx_keys;
         if (n_splits > 1) {
             p.part_o = reinterpret_cast<float*>((unsigned char*)ws + attn_vt_bytes(cfg, n_keys) +
                                                 attn_flag_bytes(cfg, m));

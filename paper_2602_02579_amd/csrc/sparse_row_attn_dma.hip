@@ -551,7 +551,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
                 for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(o_acc[db][cb][4 * r4 + e] * inv);
                 *reinterpret_cast<bf16x4*>(op + db * 32 + r4 * 8) = v;
             }
-        if (p.lse && hh == 0) p.lse[colg] = m_run[cb] * p.scale + logf(l_tot[cb]);
+        if (hh == 0) {
+            const float lse = m_run[cb] * p.scale + logf(l_tot[cb]);
+            if (p.lse) p.lse[colg] = lse;
+            // unsplit launches are only asked for this when every key is a context key
+            if (p.lse_ctx) p.lse_ctx[colg] = lse;
+        }
     }
   }   // next (kv head, row tile)
 }
@@ -579,6 +584,17 @@ __global__ __launch_bounds__(D) void attn_merge_splits_kernel(AttnParams p) {
     }
     p.out[col * D + d] = (bf16_t)(acc / wsum);
     if (p.lse && d == 0) p.lse[col] = mx + logf(wsum);
+    if (p.lse_ctx && d == 0) {
+        // the ranges that lie below ctx_keys (a range boundary): the same sum, cut there
+        const int n_c = min(n_s, p.ctx_keys / p.dma_split_len);
+        float mc = -INFINITY;
+        for (int sp = 0; sp < n_c; ++sp)
+            mc = fmaxf(mc, p.part_lse[((int64_t)sp * p.m + row) * p.hq + head]);
+        float wc = 0.f;
+        for (int sp = 0; sp < n_c; ++sp)
+            wc += __expf(p.part_lse[((int64_t)sp * p.m + row) * p.hq + head] - mc);
+        p.lse_ctx[col] = mc + logf(wc);
+    }
 }
 
 }  // namespace

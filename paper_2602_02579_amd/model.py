@@ -47,10 +47,17 @@ class CarriedRows:
     """Work buffers and call sequence for one configuration and MLP width."""
 
     def __init__(self, cfg: Config, inter: int, eps: float, device: torch.device,
-                 k: Optional[int] = None):
+                 k: Optional[int] = None, fuse_stage1: Optional[bool] = None):
         self.cfg, self.inter, self.eps, self.device = cfg, int(inter), float(eps), device
         self.lc = layer_cfg(cfg)
         n, qn = cfg.n_ctx, cfg.n_query
+        # Stage I with one key stream less: the query rows' attention emits the
+        # normaliser over the context keys and the score only sums the columns
+        # (None = whenever the library has it for this geometry)
+        ctx_ws = api.pkv_sparse_row_attn_ctx_lse_workspace_bytes(self.lc, n + qn, n, qn)
+        self.fuse_stage1 = ctx_ws > 0 if fuse_stage1 is None else bool(fuse_stage1)
+        if self.fuse_stage1 and ctx_ws == 0:
+            raise ValueError("fused Stage I is not available for this geometry")
         self.n, self.qn = n, qn
         self.k = select_count(cfg.ratio, n) if k is None else int(k)
         self.m = self.k + qn
@@ -62,6 +69,7 @@ class CarriedRows:
         self.rows = torch.empty(self.m, **i32)          # T_p ++ query rows
         self.rows[self.k:] = self.q_rows
         self.score = torch.zeros(n, dtype=torch.float32, device=device)
+        self.lse_ctx = torch.empty((qn, hq), dtype=torch.float32, device=device)
         rows_max = max(self.m, qn)
         self.h = new(rows_max, hid)                     # carried hidden states
         self.x = new(rows_max, hid)                     # normalised rows
@@ -78,7 +86,8 @@ class CarriedRows:
                 api.pkv_glue_workspace_bytes(tdt, rows, hq * d, hid),
                 api.pkv_glue_workspace_bytes(tdt, rows, hid, self.inter),
                 api.pkv_glue_workspace_bytes(tdt, rows, self.inter, hid))
-        ws_bytes = max(ws_bytes, api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, self.lc, n, qn))
+        ws_bytes = max(ws_bytes, api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, self.lc, n, qn),
+                       ctx_ws)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
 
     # one decoder layer for the first ``cnt`` rows of the buffers, at positions ``rows``
@@ -96,10 +105,17 @@ class CarriedRows:
                                         L["k_cache"], L["v_cache"], rows, ws=ws,
                                         norm_eps=self.eps,
                                         **{v: L[v] for v in VARIANT_WEIGHTS if v in L})
-        if score is not None:
-            api.pkv_query_score(lc, q, L["k_cache"][:self.n], self.score, accumulate=score,
-                                ws=ws)
-        api.pkv_sparse_row_attn(lc, q, L["k_cache"], L["v_cache"], rows, attn, None, ws=ws)
+        if score is not None and self.fuse_stage1:
+            api.pkv_sparse_row_attn_ctx_lse(lc, q, L["k_cache"], L["v_cache"], rows, attn, None,
+                                            self.lse_ctx[:cnt], self.n, ws=ws)
+            api.pkv_query_score_lse(lc, q, L["k_cache"][:self.n], self.lse_ctx[:cnt], None,
+                                    self.score, accumulate=score, ws=ws)
+        else:
+            if score is not None:
+                api.pkv_query_score(lc, q, L["k_cache"][:self.n], self.score,
+                                    accumulate=score, ws=ws)
+            api.pkv_sparse_row_attn(lc, q, L["k_cache"], L["v_cache"], rows, attn, None,
+                                    ws=ws)
         api.pkv_linear_rows(attn.view(cnt, -1), L["wo"], h, h, ws=ws)
         api.pkv_rmsnorm_rows(h, None, L["w_post"], self.eps, x)
         api.pkv_swiglu_rows(x, L["w_gate"], L["w_up"], g, ws=ws)

@@ -170,6 +170,27 @@ def oracle_attention(q, k_cache, v_cache, pos, dtype, chunk=1024):
     return np.concatenate(outs), np.concatenate(lses)
 
 
+def check_lse(cfg, sr, dev_layer, got_lse, want_lse, pos, idx=None):
+    """Log-sum-exp of the attention rows `idx` (all if None) against the oracle's.
+
+    The oracle's value comes from the oracle's own Q and cache; the device's from the
+    device's.  The two caches agree to one bf16 unit in the last place, but a row whose
+    softmax is carried by a single planted key sees such a one-unit difference of a
+    large key element in full: |q_d| * ulp(k_d) / sqrt(D) reaches 6 * 2**-5 / 11.3 =
+    1.7e-2.  So: every row within 2e-2 end to end; every row beyond 4e-3 is evaluated
+    again by the oracle on the Q, K and V the device holds and must then be within
+    4e-3 (the bound of the attention arithmetic by itself); such rows must be rare."""
+    idx = np.arange(len(pos)) if idx is None else np.asarray(idx)
+    err = np.abs(got_lse - want_lse).max(axis=1)
+    assert err.max() <= 2e-2, float(err.max())
+    far = np.nonzero(err > 4e-3)[0]
+    assert len(far) <= max(2, len(idx) // 100), len(far)
+    if len(far):
+        _, lse2 = O.sparse_row_attn(host(sr.q)[idx[far]], host(dev_layer["k_cache"]),
+                                    host(dev_layer["v_cache"]), pos[far], dtype=cfg.dtype)
+        assert np.abs(got_lse[far] - lse2).max() <= 4e-3
+
+
 def oracle_layer_cache(cfg, L, rows):
     """Oracle K/V of all recomputed rows and the updated caches of one layer."""
     n, qn = cfg.n_ctx, cfg.n_query
@@ -227,7 +248,7 @@ def test_config3_full_size_every_row_against_the_oracle(gpu_device):
     # per row as well: a dropped or doubled tile would not hide behind the largest row
     row_err = np.abs(got_out - out).max(axis=(1, 2)) / np.abs(out).max(axis=(1, 2))
     assert row_err.max() <= 3e-2, (int(row_err.argmax()), float(row_err.max()))
-    assert np.abs(got_lse - lse).max() <= 4e-3
+    check_lse(cfg, sr, dev_layers[0], got_lse, lse, rows)
 
 
 _CFG4_BASE = {}
@@ -279,4 +300,4 @@ def test_config4_full_size_three_of_the_32_layers_two_fused_scoring_layers(gpu_d
                                 cfg.dtype)
     assert rel_err(host(sr.q)[pick], q[pick]) <= TOL[cfg.dtype]
     assert rel_err(host(sr.out)[pick], out) <= TOL[cfg.dtype]
-    assert np.abs(host(sr.lse)[pick] - lse).max() <= 4e-3
+    check_lse(cfg, sr, dev_layers[-1], host(sr.lse)[pick], lse, rows[pick], pick)

@@ -135,9 +135,21 @@ def test_whole_path_at_131k_with_26470_recomputed_rows(gpu_device):
                                      g.choice(m, 32, replace=False)]))
     got_q, got_out, got_lse = host(sr.q)[pick], host(sr.out)[pick], host(sr.lse)[pick]
     assert np.abs(got_q - q[pick]).max() / np.abs(q[pick]).max() <= 2e-2
+    far = []
     for a in range(0, len(pick), 128):          # bounded [rows, keys] temporaries
         sl = slice(a, a + 128)
         want, want_lse = O.sparse_row_attn(q[pick[sl]], k_cache, v_cache, rows[pick[sl]],
                                            dtype="bf16")
         assert np.abs(got_out[sl] - want).max() / np.abs(want).max() <= 2e-2
-        assert np.abs(got_lse[sl] - want_lse).max() <= 4e-3
+        err = np.abs(got_lse[sl] - want_lse).max(axis=1)
+        assert err.max() <= 2e-2
+        far.extend(a + np.nonzero(err > 4e-3)[0])
+    # rows beyond the bound of the attention arithmetic itself (4e-3) owe it to a
+    # one-unit bf16 difference between the two caches in a large element of a key that
+    # carries their softmax: on the Q, K and V the device holds they must meet it
+    assert len(far) <= max(2, len(pick) // 100)
+    if far:
+        far = np.asarray(far)
+        _, lse2 = O.sparse_row_attn(host(sr.q)[pick[far]], kc, vc, rows[pick[far]],
+                                    dtype="bf16")
+        assert np.abs(got_lse[far] - lse2).max() <= 4e-3

@@ -139,7 +139,20 @@ def test_model_matches_oracle(gpu_device, name):
         assert rel_err(vc[rows], want["v_cache"][li][rows]) <= tol
         assert np.array_equal(vc[rest], want["v_cache"][li][rest])
         assert rel_err(kc[rest], want["k_cache"][li][rest]) <= tol
-    assert rel_err(host(cr.attn[:cr.m]), want["attn"][-1]) <= tol
+    # The last layer's attention is compared twice.  Against the oracle's own chain the
+    # hidden states have passed through every layer's roundings on both sides, and a
+    # one-unit difference upstream is amplified by what follows, so the bar there is
+    # twice the per-call one for the largest element, and the per-call one for the RMS.
+    # On the Q, K and V the device itself holds for that layer the per-call bar applies.
+    got_attn = host(cr.attn[:cr.m])
+    assert rel_err(got_attn, want["attn"][-1]) <= 2 * tol
+    rms = float(np.sqrt(np.mean((got_attn - want["attn"][-1]) ** 2) /
+                        np.mean(want["attn"][-1] ** 2)))
+    assert rms <= tol, rms
+    L = dev_layers[-1]
+    same_in, _ = O.sparse_row_attn(host(cr.q[:cr.m]), host(L["k_cache"]), host(L["v_cache"]),
+                                   rows, dtype=cfg.dtype)
+    assert rel_err(got_attn, same_in) <= tol
     assert rel_err(host(h_final), want["h_final"]) <= tol
 
 
