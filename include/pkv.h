@@ -140,6 +140,30 @@ pkv_status pkv_query_score(const pkv_layer_cfg* cfg,
                            void* stream);
 
 /*
+ * pkv_query_score for callers that cannot allocate device memory or pass a
+ * workspace: code recorded into a HIP graph, tight serving loops, harnesses that
+ * forbid allocation.  Same arguments, kernels and results (bit for bit) as
+ * pkv_query_score, without `ws`: the scratch is a PKV_STATIC_SCRATCH_BYTES array
+ * inside the library, one copy per GPU, held until the process ends.  The call
+ * allocates nothing and frees nothing.  A problem that needs more scratch than
+ * that - pkv_workspace_bytes(PKV_CALL_QUERY_SCORE, cfg, n_ctx, nq) tells - returns
+ * PKV_ERR_WORKSPACE and enqueues nothing (16 MiB cover 32k context keys with 128
+ * query tokens of 32 heads; 128k keys with 256 query tokens need 68 MB and are
+ * refused).  The first call on a device looks the array's address up
+ * (make it outside a graph capture); the device must be current.  All calls on one
+ * GPU share the array: calls that can overlap there (different streams, or graphs
+ * replayed concurrently) race on it - order them, or use pkv_query_score with
+ * workspaces of their own.
+ */
+#define PKV_STATIC_SCRATCH_BYTES (16u << 20)
+pkv_status pkv_query_score_static(const pkv_layer_cfg* cfg,
+                                  const void* q,      /* [nq, Hq, D]     */
+                                  const void* k,      /* [n_ctx, Hkv, D] */
+                                  float* score,       /* [n_ctx]         */
+                                  int64_t nq, int64_t n_ctx, float softmax_scale,
+                                  int accumulate, void* stream);
+
+/*
  * Step 3 - top-p selection (paper: Eq. 4, TOP_p of the value function;
  * Algorithm 1 "Select token indices"; Sec. 4.3: one set for all layers).
  *

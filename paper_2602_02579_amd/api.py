@@ -17,7 +17,7 @@ from typing import Optional
 import torch
 
 __all__ = ["LayerCfg", "PkvError", "load_library", "library_path",
-           "pkv_rope_restore", "pkv_query_score",
+           "pkv_rope_restore", "pkv_query_score", "pkv_query_score_static",
            "pkv_query_score_lse", "pkv_sparse_row_attn_ctx_lse",
            "pkv_sparse_row_attn_ctx_lse_workspace_bytes",
            "pkv_topk_select", "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex",
@@ -31,8 +31,10 @@ PKV_F32, PKV_BF16 = 0, 1
 CALL_ROPE_RESTORE, CALL_QUERY_SCORE, CALL_TOPK_SELECT = 1, 2, 3
 CALL_GATHER_QKV_PROJ, CALL_SCATTER_KV, CALL_SPARSE_ROW_ATTN = 4, 5, 6
 
+STATIC_SCRATCH_BYTES = 16 << 20   # PKV_STATIC_SCRATCH_BYTES of the header
+
 EXPORTED_SYMBOLS = [
-    "pkv_rope_restore", "pkv_query_score", "pkv_topk_select",
+    "pkv_rope_restore", "pkv_query_score", "pkv_query_score_static", "pkv_topk_select",
     "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex", "pkv_gather_qkv_proj_scatter",
     "pkv_scatter_kv", "pkv_sparse_row_attn", "pkv_rmsnorm_rows", "pkv_gather_rows", "pkv_linear_rows", "pkv_swiglu_rows",
     "pkv_glue_workspace_bytes", "pkv_query_score_lse", "pkv_sparse_row_attn_ctx_lse",
@@ -106,6 +108,8 @@ def load_library() -> ctypes.CDLL:
     lib.pkv_rope_restore.argtypes = [cfgp, vp, vp, i32p, i64, i64, vp]
     lib.pkv_query_score.argtypes = [cfgp, vp, vp, f32p, i64, i64, ctypes.c_float,
                                     ctypes.c_int, vp, ctypes.c_size_t, vp]
+    lib.pkv_query_score_static.argtypes = [cfgp, vp, vp, f32p, i64, i64, ctypes.c_float,
+                                           ctypes.c_int, vp]
     lib.pkv_topk_select.argtypes = [f32p, i64, i64, i32p, vp, ctypes.c_size_t, vp]
     lib.pkv_query_score_lse.argtypes = [cfgp, vp, vp, f32p, i32p, f32p, i64, i64,
                                         ctypes.c_float, ctypes.c_int, vp, ctypes.c_size_t, vp]
@@ -134,7 +138,7 @@ def load_library() -> ctypes.CDLL:
                                     ctypes.c_size_t, vp]
     lib.pkv_glue_workspace_bytes.argtypes = [i32, i64, i64, i64]
     lib.pkv_glue_workspace_bytes.restype = ctypes.c_size_t
-    for name in ("pkv_rope_restore", "pkv_query_score",
+    for name in ("pkv_rope_restore", "pkv_query_score", "pkv_query_score_static",
                  "pkv_topk_select", "pkv_query_score_lse", "pkv_sparse_row_attn_ctx_lse",
                  "pkv_gather_qkv_proj", "pkv_gather_qkv_proj_ex",
                  "pkv_gather_qkv_proj_scatter", "pkv_scatter_kv",
@@ -224,6 +228,24 @@ def pkv_query_score(cfg: LayerCfg, q: torch.Tensor, k: torch.Tensor,
         ctypes.byref(c), _ptr(q, cfg.torch_dtype, "q"), _ptr(k, cfg.torch_dtype, "k"),
         _ptr(score, torch.float32, "score"), nq, n_ctx, float(softmax_scale),
         int(bool(accumulate)), wp, wb, _stream()))
+
+
+def pkv_query_score_static(cfg: LayerCfg, q: torch.Tensor, k: torch.Tensor,
+                           score: torch.Tensor, accumulate: bool = False,
+                           softmax_scale: float = 0.0) -> None:
+    """pkv_query_score without a workspace (scratch inside the library)."""
+    nq, n_ctx = q.shape[0], k.shape[0]
+    if tuple(q.shape) != (nq, cfg.n_q_heads, cfg.head_dim):
+        raise ValueError("q must be [nq, Hq, D]")
+    if tuple(k.shape) != (n_ctx, cfg.n_kv_heads, cfg.head_dim):
+        raise ValueError("k must be [n_ctx, Hkv, D]")
+    if tuple(score.shape) != (n_ctx,):
+        raise ValueError("score must be [n_ctx]")
+    c = cfg._c()
+    _check("pkv_query_score_static", load_library().pkv_query_score_static(
+        ctypes.byref(c), _ptr(q, cfg.torch_dtype, "q"), _ptr(k, cfg.torch_dtype, "k"),
+        _ptr(score, torch.float32, "score"), nq, n_ctx, float(softmax_scale),
+        int(bool(accumulate)), _stream()))
 
 
 def pkv_topk_select(score: torch.Tensor, k: int, idx_out: torch.Tensor,

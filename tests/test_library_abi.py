@@ -75,6 +75,10 @@ def test_argument_errors_are_reported_without_a_gpu():
                                    4, (1 << 24) - 64, 0.0, None, 0, None) == 1
     assert lib.pkv_sparse_row_attn(ctypes.byref(c), None, None, None, None, None, None,
                                    1 << 27, 1024, 0.0, None, 0, None) == 3
+    # the entry point with built-in scratch refuses what does not fit it, before any device call
+    assert lib.pkv_query_score_static(None, None, None, None, 128, 32768, 0.0, 0, None) == 1
+    assert lib.pkv_query_score_static(ctypes.byref(c), None, None, None, 256, 131072, 0.0, 0,
+                                      None) == 4
     wide = api.LayerCfg(4096, 8, 128, 4096, 5e5, "bf16")._c()
     assert lib.pkv_query_score(ctypes.byref(wide), None, None, None, 1 << 20, 1024, 0.0, 0,
                                None, 0, None) == 3
