@@ -11,8 +11,15 @@ a small stacked model with the hidden states carried through the layers - Stage 
 the query rows, Stage II on the selected + query rows, each layer with its output
 projection and gated MLP (Llama-3-8B widths) - and reports it as `carried_model`.
 
+Also outside `value`: `extras` (the same pass at ratios 0.1 / 0.4, at 8k and 128k
+context and through a 32-layer stack with scoring fused over 2 layers, all on device-side
+random draws), `bandwidth` (the HBM-bound calls cold - rotating over more than 512 MB of
+buffers so that the 256 MB Infinity Cache cannot serve them - and warm, next to a plain
+copy measured the same way) and `diagnostics` (selection overlap ratios of Sec. 3.1 on a
+small random model, planted-token hit rates of two criteria at the benchmark shape).
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
-                    [--no-cpu-baseline] [--model-layers L]
+                    [--no-cpu-baseline] [--model-layers L] [--no-extras]
 """
 
 from __future__ import annotations
@@ -37,6 +44,8 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/hot_path_cfg3_hbm_traffic.txt
 # (counters cannot be read from inside this process; the figure is for that workload only)
 MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 1.969e9}
+TRAFFIC_SOURCE = ("profiles/hot_path_cfg3_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / "
+                  "WRITE_SIZE of `bench.py --profile-call sparse_row_attn`, not read live)")
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
@@ -74,24 +83,60 @@ def gpu_callables(cfg, layer, device):
 
 
 def build_gpu_workload(cfg, device):
-    layers = []
+    """The seeded host draws with plants for the scoring layers; the layers behind them
+    (config 4 has 30 more) only feed Stage II and are drawn on the device, same
+    distributions, to keep the set-up short.  Returns the layers and the plant index sets
+    of the first layer."""
+    layers, plants = [], None
     for li in range(cfg.n_layers):
+        if li >= cfg.n_score_layers:
+            layers.extend(random_layers(cfg, device, cfg.n_layers - li, seed=100 + cfg.seed))
+            break
         layer = synth.make_layer(cfg, li)
-        if li < cfg.n_score_layers:
-            pq, rot = gpu_callables(cfg, layer, device)
-            synth.plant(cfg, layer, li, pq, rot)
+        pq, rot = gpu_callables(cfg, layer, device)
+        info = synth.plant(cfg, layer, li, pq, rot)
+        if li == 0:
+            plants = dict(relevant=info["relevant"], salient=info["salient"])
         layers.append(pipeline.upload_layer(cfg, layer, device))
         del layer
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
-    return layers
+    return layers, plants
+
+
+def random_layers(cfg, device, n_layers, seed):
+    """Hot-path layers drawn on the device (the distributions of synth.make_layer, nothing
+    planted): for the workloads outside `value`, where only the shapes matter."""
+    dt = pipeline.layer_cfg(cfg).torch_dtype
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    n, qn = cfg.n_ctx, cfg.n_query
+    hq, hkv, d, hid = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.hidden
+
+    def normal(*shape, scale=1.0):
+        return (torch.randn(shape, generator=gen, device=device) * scale).to(dt)
+
+    out = []
+    for _ in range(n_layers):
+        hidden = torch.randn((n + qn, hid), generator=gen, device=device)
+        hidden[:n] += 0.5 * torch.randn(hid, generator=gen, device=device)
+        hidden[n:] = torch.randn(hid, generator=gen, device=device) + 0.3 * hidden[n:]
+        L = dict(k_nope=normal(n, hkv, d), hidden=hidden.to(dt),
+                 wq=normal(hq * d, hid, scale=0.02), wk=normal(hkv * d, hid, scale=0.02),
+                 wv=normal(hkv * d, hid, scale=0.02),
+                 v_cache=torch.zeros((n + qn, hkv, d), dtype=dt, device=device),
+                 k_cache=torch.zeros((n + qn, hkv, d), dtype=dt, device=device))
+        L["v_cache"][:n] = normal(n, hkv, d)
+        del hidden
+        out.append(L)
+    return out
 
 
 # --------------------------------------------------------------------------
 # CPU baseline: the oracle as it stands, on a bounded sample
 # --------------------------------------------------------------------------
 
-def cpu_baseline(cfg, row_stride=2):
+def cpu_baseline(cfg, row_stride=1):
     """Times the CPU oracle on the same seeded workload.  Restore, query
     projection, score and selection run in full; the row-wise steps
     (projection, scatter, attention) run on every `row_stride`-th recomputed
@@ -150,9 +195,12 @@ def cpu_baseline(cfg, row_stride=2):
     return {
         "value": len(rows) / full, "unit": "tokens/s", "cores": int(threads),
         "kind": "oracle",
-        "sample": (f"restore, query projection, score, top-k in full; projection and "
-                   f"attention on every {row_stride}th of the {len(rows)} recomputed rows "
-                   f"({len(sample)} rows), scaled by {scale:.1f}; "
+        "sample": (f"one layer of {cfg.name}: restore, query projection, score, top-k in full; "
+                   f"projection, scatter and attention on " +
+                   (f"all {len(rows)} recomputed rows (nothing sampled or scaled); "
+                    if row_stride == 1 else
+                    f"every {row_stride}th of the {len(rows)} recomputed rows "
+                    f"({len(sample)} rows), scaled by {scale:.1f}; ") +
                    f"measured {sum(t.values()):.1f} s of CPU work"),
         "seconds": {name: round(v, 3) for name, v in t.items()},
     }
@@ -181,6 +229,197 @@ def time_calls(fn, reps, batch=10):
         e.synchronize()
         ts.append(s.elapsed_time(e) * 1e-3 / batch)
     return float(np.median(ts))
+
+
+def timed_passes(sr, layers, steps):
+    """Exactly `steps` passes of the hot path between synchronisations; every
+    pkv_sparse_row_attn call inside them is bracketed by events on the launch stream.
+    Returns (seconds elapsed, mean seconds per attention call)."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps * len(layers))]
+    orig_attn = api.pkv_sparse_row_attn
+    counter = [0]
+
+    def timed_attn(*a, **kw):
+        s, e = ev[counter[0]]
+        counter[0] += 1
+        s.record()
+        orig_attn(*a, **kw)
+        e.record()
+    pipeline.api.pkv_sparse_row_attn = timed_attn
+    try:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            sr.run(layers)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    finally:
+        pipeline.api.pkv_sparse_row_attn = orig_attn
+    return elapsed, float(np.mean([s.elapsed_time(e) for s, e in ev])) * 1e-3
+
+
+def extra_workload(name, cfg, device, steps=3, warmup=1, seed=77):
+    """One more workload through the same pass, on device-side random draws."""
+    layers = random_layers(cfg, device, cfg.n_layers, seed)
+    sr = pipeline.SelectiveRecompute(cfg, device)
+    for _ in range(warmup):
+        sr.run(layers)
+    elapsed, t_attn = timed_passes(sr, layers, steps)
+    flops = attn_flops(sr.rows.cpu().numpy(), cfg.n_q_heads, cfg.head_dim)
+    L = layers[0]
+    small = {
+        "rope_restore_us": time_calls(lambda: sr.restore(L), 3) * 1e6,
+        "query_proj+query_score_us": time_calls(lambda: sr.score_layer(L, False), 3) * 1e6,
+        "topk_select_us": time_calls(lambda: sr.select(), 3) * 1e6,
+        "gather_qkv_proj_us": time_calls(lambda: api.pkv_gather_qkv_proj(
+            sr.lc, L["hidden"], sr.rows, sr.rows, L["wq"], L["wk"], L["wv"], sr.q, sr.k_new,
+            sr.v_new, ws=sr.ws), 3, batch=4) * 1e6,
+        "scatter_kv_us": time_calls(lambda: api.pkv_scatter_kv(
+            sr.lc, sr.k_new, sr.v_new, sr.rows, L["k_cache"], L["v_cache"]), 3) * 1e6,
+    }
+    per_pass = elapsed / steps
+    out = {"workload": name, "n_ctx": cfg.n_ctx, "n_query": cfg.n_query, "ratio": cfg.ratio,
+           "rows_recomputed": sr.m, "layers": len(layers),
+           "n_score_layers": min(cfg.n_score_layers, len(layers)),
+           "ms_per_pass": round(per_pass * 1e3, 4),
+           "recomputed_tokens_per_s": round(sr.m * len(layers) / per_pass, 1),
+           "sparse_row_attn_us": round(t_attn * 1e6, 1),
+           "sparse_row_attn_tflops": round(flops / t_attn / 1e12, 2),
+           "sparse_row_attn_frac": round(flops / t_attn / 1e12 / PEAK_BF16_TFLOPS, 4),
+           "data": "synthetic (device-side seeded normal draws, nothing planted)"}
+    out.update({k: round(v, 1) for k, v in small.items()})
+    del layers, sr
+    torch.cuda.empty_cache()
+    return out
+
+
+def extras(device):
+    """The other workloads of the list: ratios 0.1 / 0.4 at the benchmark shape, the
+    8k and the 128k context, and the 32-layer stack with scoring fused over 2 layers at
+    three ratios (the hidden states are supplied per layer, as in the timed pass)."""
+    c3, c4 = synth.CONFIGS[3], synth.CONFIGS[4]
+    todo = [("cfg3-shape r=0.1", c3.with_(ratio=0.1)), ("cfg3-shape r=0.4", c3.with_(ratio=0.4)),
+            ("cfg2 8k r=0.2", synth.CONFIGS[2]), ("cfg5 128k r=0.2", synth.CONFIGS[5])]
+    todo += [(f"cfg4 32 layers r={r}", c4.with_(ratio=r)) for r in (0.1, 0.2, 0.4)]
+    return [extra_workload(name, cfg, device, steps=2 if cfg.n_layers > 1 else 3)
+            for name, cfg in todo]
+
+
+def bandwidth(cfg, device, reps=5):
+    """The HBM-bound calls and a plain copy, warm (one buffer set over and over: what fits
+    the 256 MB Infinity Cache is served from it) and cold (a rotation over buffer sets whose
+    touched bytes add up to more than 512 MB between two visits of the same set)."""
+    lc = pipeline.layer_cfg(cfg)
+    dt = lc.torch_dtype
+    n, qn = cfg.n_ctx, cfg.n_query
+    hkv, d, hid = cfg.n_kv_heads, cfg.head_dim, cfg.hidden
+    m = synth.select_count(cfg.ratio, n) + qn
+    row_b = hkv * d * 2
+    rows = torch.sort(torch.randperm(n + qn, device=device)[:m])[0].to(torch.int32)
+
+    def new(*shape):
+        return torch.randn(shape, device=device).to(dt)
+
+    w_norm = torch.ones(hid, dtype=dt, device=device)
+    calls = {
+        "rope_restore": (lambda: (new(n, hkv, d), torch.empty((n, hkv, d), dtype=dt, device=device)),
+                         lambda b: api.pkv_rope_restore(lc, b[0], b[1], None, 0),
+                         2.0 * n * row_b),
+        "scatter_kv": (lambda: (new(m, hkv, d), new(m, hkv, d), new(n + qn, hkv, d),
+                                new(n + qn, hkv, d)),
+                       lambda b: api.pkv_scatter_kv(lc, b[0], b[1], rows, b[2], b[3]),
+                       4.0 * m * row_b),
+        "gather_rows": (lambda: (new(n + qn, hid), torch.empty((m, hid), dtype=dt, device=device)),
+                        lambda b: api.pkv_gather_rows(b[0], rows, b[1]),
+                        2.0 * m * hid * 2),
+        "rmsnorm_rows": (lambda: (new(m, hid), torch.empty((m, hid), dtype=dt, device=device)),
+                         lambda b: api.pkv_rmsnorm_rows(b[0], None, w_norm, 1e-5, b[1]),
+                         2.0 * m * hid * 2),
+        "plain_copy_same_bytes_as_rope_restore": (
+            lambda: (new(n, hkv, d), torch.empty((n, hkv, d), dtype=dt, device=device)),
+            lambda b: b[1].copy_(b[0]), 2.0 * n * row_b),
+    }
+    out = {}
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for name, (make, call, nbytes) in calls.items():
+        n_sets = max(2, int(np.ceil(640e6 / nbytes)) + 1)
+        sets = [make() for _ in range(n_sets)]
+        for b in sets:
+            call(b)
+        torch.cuda.synchronize()
+        warm = time_calls(lambda: call(sets[0]), reps)
+        ts = []
+        for _ in range(reps):
+            s.record()
+            for b in sets:
+                call(b)
+            e.record()
+            e.synchronize()
+            ts.append(s.elapsed_time(e) * 1e-3 / n_sets)
+        cold = float(np.median(ts))
+        out[name] = {"bytes": nbytes, "buffer_sets": n_sets,
+                     "warm_us": round(warm * 1e6, 1),
+                     "warm_GB/s": round(nbytes / warm / 1e9, 1),
+                     "warm_frac": round(nbytes / warm / 1e9 / PEAK_HBM_GBS, 4),
+                     "cold_us": round(cold * 1e6, 1),
+                     "cold_GB/s": round(nbytes / cold / 1e9, 1),
+                     "cold_frac": round(nbytes / cold / 1e9 / PEAK_HBM_GBS, 4)}
+        del sets
+        torch.cuda.empty_cache()
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=device)
+    big2 = torch.empty_like(big)
+    t = time_calls(lambda: big2.copy_(big), 3, batch=3)
+    out["plain_copy_1GiB"] = {"bytes": 2.0 * (1 << 30), "cold_us": round(t * 1e6, 1),
+                              "cold_GB/s": round(2.0 * (1 << 30) / t / 1e9, 1),
+                              "cold_frac": round(2.0 * (1 << 30) / t / 1e9 / PEAK_HBM_GBS, 4)}
+    return out
+
+
+def diagnostics_report(device, layer, plants, sr):
+    """(1) Hit rates of the planted tokens under two criteria at the timed workload: the
+    user-query score the pass selected with, and the global column sum of Appendix B,
+    Tab. 3 (the attention a token receives from all rows).  (2) Overlap ratios of
+    Sec. 3.1 and the chunk-size sweep of Sec. 5.5 on a small random model."""
+    from paper_2602_02579_amd import diagnostics
+    out = {}
+    cfg = sr.cfg
+    if plants is not None:
+        dg = diagnostics.Diagnostics(cfg, 64, 1e-5, device)
+        t0 = time.perf_counter()
+        beta = dg.column_sum_from_hidden(layer["hidden"], layer, layer["k_nope"],
+                                         layer["v_cache"][:cfg.n_ctx])
+        by_colsum = diagnostics.top_indices(beta, sr.k).cpu().numpy()
+        torch.cuda.synchronize()
+        by_query = sr.rows[:sr.k].cpu().numpy()
+        rel, sal = plants["relevant"], plants["salient"]
+        out["planted_tokens"] = {
+            "workload": cfg.name, "ratio": cfg.ratio,
+            "query_relevant_selected": {"query_score": float(np.isin(rel, by_query).mean()),
+                                        "global_column_sum": float(np.isin(rel, by_colsum).mean())},
+            "globally_salient_selected": {"query_score": float(np.isin(sal, by_query).mean()),
+                                          "global_column_sum": float(np.isin(sal, by_colsum).mean())},
+            "column_sum_pass_ms": round((time.perf_counter() - t0) * 1e3, 1)}
+        del dg, beta
+    small = synth.Config("diag-model", "bf16", 8, 256, 32, 8, 2, 128, 1024, 500000.0, seed=31,
+                         n_layers=4, n_score_layers=4)
+    inter = 2048
+    dt = torch.bfloat16
+    embed = torch.from_numpy(synth.make_embed(small)).to(dt).to(device)
+    blocks = [{k: torch.from_numpy(v).to(dt).to(device)
+               for k, v in synth.make_block_weights(small, li, inter).items()}
+              for li in range(small.n_layers)]
+    dg = diagnostics.Diagnostics(small, inter, 1e-5, device)
+    ratios = [0.1, 0.2, 0.4]
+    sweep = {}
+    for chunk_len in (64, 128, 256, 512, 2048):
+        res = dg.selection_diagnostics(embed, blocks, chunk_len, ratios)
+        sweep[str(chunk_len)] = {name: [round(x, 4) for x in res[name]]
+                                 for name in ("fused", "first_layer", "column_sum")}
+    out["overlap_with_full_prefill_query_attention"] = {
+        "model": "4 random layers, 2048 context tokens, 32 query tokens, 8/2 heads, hidden 1024",
+        "ratios": ratios, "by_chunk_len": sweep}
+    return out
 
 
 def carried_model(cfg, device, n_layers, inter=14336, eps=1e-5, steps=3):
@@ -217,13 +456,25 @@ def carried_model(cfg, device, n_layers, inter=14336, eps=1e-5, steps=3):
         layers.append(L)
     embed = normal(n + qn, hid)
     cr = model.CarriedRows(cfg, inter, eps, device)
-    cr.run(embed, layers)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
+    # Stage II writes the recomputed values into v_cache: every timed pass starts from the
+    # assembled chunk values again (copied back outside the timed interval), so each one is
+    # the first-pass problem; the keys are restored from k_nope by the pass itself
+    pristine = [L["v_cache"].clone() for L in layers]
+    per_pass = []
+    sel = []
+    for it in range(steps + 1):                 # the first pass warms up
+        for L, v0 in zip(layers, pristine):
+            L["v_cache"].copy_(v0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         h = cr.run(embed, layers)
-    torch.cuda.synchronize()
-    per_pass = (time.perf_counter() - t0) / steps
+        torch.cuda.synchronize()
+        if it:
+            per_pass.append(time.perf_counter() - t0)
+        sel.append(cr.rows.clone())
+    per_pass = float(np.median(per_pass))
+    same_selection = all(torch.equal(sel[0], x) for x in sel[1:])
+    del pristine
     finite = bool(torch.isfinite(h.float()).all())
     # the glue calls of one Stage II layer, one by one
     m = cr.m
@@ -254,7 +505,9 @@ def carried_model(cfg, device, n_layers, inter=14336, eps=1e-5, steps=3):
             "rows_stage2": m, "rows_stage1": qn, "ms_per_pass": round(per_pass * 1e3, 3),
             "ms_per_layer_stage2_est": round(sum(v["us"] for v in glue.values()) * 1e-3, 3),
             "recomputed_tokens_per_s": round(m * n_layers / per_pass, 1),
-            "output_finite": finite, "data": "synthetic (device-side seeded normal draws)",
+            "output_finite": finite, "same_selection_every_pass": same_selection,
+            "fused_stage1": cr.fuse_stage1,
+            "data": "synthetic (device-side seeded normal draws)",
             "glue": glue}
 
 
@@ -271,6 +524,9 @@ def main():
                          "topk_select, gather_qkv_proj, scatter_kv, sparse_row_attn; or "
                          "copy = a plain 1 GiB device copy that calibrates the HBM counters")
     ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the other workloads, the cold/warm bandwidth table and the "
+                         "diagnostics")
     ap.add_argument("--model-layers", type=int, default=4,
                     help="layers of the carried-hidden-state model timed after the steps "
                          "(0 = skip); bf16 configurations with head_dim 128 only")
@@ -284,9 +540,7 @@ def main():
     device = torch.device("cuda:0")
     torch.cuda.set_device(device)
     cfg = synth.CONFIGS[args.config]
-    if cfg.n_layers > 4:
-        cfg = cfg.with_(n_layers=4)   # bounded memory for the stacked config
-    layers = build_gpu_workload(cfg, device)
+    layers, plants = build_gpu_workload(cfg, device)
     sr = pipeline.SelectiveRecompute(cfg, device)
 
     for _ in range(args.warmup):
@@ -319,26 +573,7 @@ def main():
 
     # ---- timed region: exactly K steps; the dominant kernel (step 5) is
     # bracketed by events on the launch stream inside it ---------------------
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps * len(layers))]
-    orig_attn = api.pkv_sparse_row_attn
-    counter = [0]
-
-    def timed_attn(*a, **kw):
-        s, e = ev[counter[0]]
-        counter[0] += 1
-        s.record()
-        orig_attn(*a, **kw)
-        e.record()
-    pipeline.api.pkv_sparse_row_attn = timed_attn
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        sr.run(layers)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    pipeline.api.pkv_sparse_row_attn = orig_attn
-    t_attn = float(np.mean([s.elapsed_time(e) for s, e in ev])) * 1e-3
+    elapsed, t_attn = timed_passes(sr, layers, args.steps)
 
     ms_per_step = elapsed / args.steps * 1e3
     m_rows = sr.m * len(layers)
@@ -383,7 +618,8 @@ def main():
         breakdown[name] = entry
 
     result = {
-        "metric": "recomputed tokens/s (selective-recompute hot path, 32k ctx, r=0.2)",
+        "metric": (f"recomputed tokens/s (selective-recompute hot path, "
+                   f"{cfg.n_ctx // 1024}k ctx, r={cfg.ratio})"),
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
@@ -401,7 +637,10 @@ def main():
                      "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
                      "frac": round(achieved / peak, 4),
                      "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(cfg.name),
-                     "flops_per_launch": flops, "avg_launch_s": t_attn},
+                     "traffic_source": TRAFFIC_SOURCE,
+                     "flops_per_launch": flops, "avg_launch_s": t_attn,
+                     "launch": "pkv_sparse_row_attn = V^T pre-pass + attn_dma128_kernel + "
+                               "repair pass, timed with events on the launch stream"},
         "breakdown": breakdown,
     }
     # the same pass with steps 4a + 4b fused into one call (outside `value`)
@@ -415,10 +654,16 @@ def main():
     result["ms_per_step_fused_cache_update"] = round(
         (time.perf_counter() - t0) / args.steps * 1e3, 4)
     del sr_f
+    if not args.no_extras and cfg.dtype == "bf16":
+        result["diagnostics"] = diagnostics_report(device, layers[0], plants, sr)
+    del layers, sr
+    torch.cuda.empty_cache()
+    if not args.no_extras and cfg.dtype == "bf16":
+        result["bandwidth"] = bandwidth(cfg, device)
+        result["extras"] = extras(device)
     if args.model_layers > 0 and cfg.dtype == "bf16":
-        del layers, sr
-        torch.cuda.empty_cache()
-        result["carried_model"] = carried_model(cfg, device, args.model_layers)
+        result["carried_model"] = carried_model(cfg.with_(n_layers=1), device,
+                                                args.model_layers)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg.with_(n_layers=1, n_score_layers=1))
     print(json.dumps(result))
