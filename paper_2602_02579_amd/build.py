@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(HERE, "libpkv.so")
 SOURCES = ["pkv_api.hip", "rope_restore.hip", "query_score.hip", "query_score_dma.hip",
            "topk_select.hip", "gather_qkv_proj.hip", "gather_qkv_proj_dma.hip",
            "scatter_kv.hip", "layer_glue.hip", "static_scratch.hip",
-           "sparse_row_attn.hip", "sparse_row_attn_dma.hip"]
+           "sparse_row_attn.hip", "sparse_row_attn_dma.hip", "sparse_row_attn_w8.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -34,6 +34,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 # registers
 SOURCE_FLAGS = {
     "sparse_row_attn_dma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "sparse_row_attn_w8.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }
 
 

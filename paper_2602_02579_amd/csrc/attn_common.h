@@ -39,5 +39,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // head_dim 128 attention proper: software-pipelined, K / V^T tiles brought
 // into LDS by direct global->LDS loads (sparse_row_attn_dma.hip)
 pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st);
+// its main kernel with eight waves of 32 columns per workgroup (sparse_row_attn_w8.hip)
+pkv_status launch_attn_w8_main(const AttnParams& p, int n_cu, hipStream_t st);
 
 }  // namespace pkv

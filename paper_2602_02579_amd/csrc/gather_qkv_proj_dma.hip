@@ -462,7 +462,10 @@ __global__ __launch_bounds__(256) void proj_dma_kernel(ProjParams p, int n_tok_t
 // needs four feature units W0..W3 (tile rows 64 i ..) and four token units X0..X3, where
 // X_q holds the rows both token halves consume in quarter q of the step: tile rows
 // 32 q .. + 32 and 128 + 32 q .. + 32.  Units of step T sit in slots 8 (T & 1) + (0..7).
-// The 16-byte chunk c of unit row r is stored at position c ^ (r & 7).
+// The 16-byte chunk c of unit row r is stored at position c ^ ((r >> 1) & 7): two 128-byte
+// rows span the 64 banks, so the sixteen lanes that an operand read serves per clock (rows
+// r .. r + 15, one logical chunk) must differ in (r & 1, position) - with c ^ (r & 7) rows r
+// and r + 8 met in one bank group and every read took two passes (SQ_LDS_BANK_CONFLICT).
 //
 // A step is 64 MFMAs per wave in four quarters; quarter q multiplies the wave's four
 // feature blocks by its token block q for all four 16-wide sub-steps.  The feature
@@ -513,9 +516,9 @@ __global__ __launch_bounds__(256) void proj_slab_kernel(ProjParams p, int n_tok_
     const int k_begin = split * n_T * 64;
 
     // ---- fill side: wave w issues instructions j = 0, 1 of every unit: unit rows
-    // 8 (2 w + j) .. + 8; lane = (row in the eight, position), fetching chunk pos ^ row
+    // 8 (2 w + j) .. + 8; lane = (row in the eight, position), fetching the chunk that
+    // belongs at that position: pos ^ ((unit row >> 1) & 7) = pos ^ (4 j + (row >> 1))
     const int rl = lane >> 3;
-    const int gchunk = (lane & 7) ^ rl;
     const bf16_t* wptr[4][2];
     const bf16_t* xptr[4][2];
 #pragma unroll
@@ -523,6 +526,7 @@ __global__ __launch_bounds__(256) void proj_slab_kernel(ProjParams p, int n_tok_
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int ur = 8 * (2 * wave + j) + rl;   // row inside the unit
+            const int gchunk = (lane & 7) ^ ((ur >> 1) & 7);
             const int r = 64 * i + ur;                // feature row of the tile
             if (MODE == kProjGated) {
                 const int f = ft * 128 + (r >> 7) * 64 + (r & 63);
@@ -555,7 +559,7 @@ __global__ __launch_bounds__(256) void proj_slab_kernel(ProjParams p, int n_tok_
     for (int par = 0; par < 2; ++par)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            const uint32_t swz = (uint32_t)(((2 * ks + hh) ^ (l32 & 7)) * 16);
+            const uint32_t swz = (uint32_t)(((2 * ks + hh) ^ ((l32 >> 1) & 7)) * 16);
             base_w[par][ks] = par * 8 * kUnitBytes + 2 * wf * kUnitBytes + l32 * 128 + swz;
             base_x[par][ks] = par * 8 * kUnitBytes + 4 * kUnitBytes + (wt * 32 + l32) * 128 + swz;
         }

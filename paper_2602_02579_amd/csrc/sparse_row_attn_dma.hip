@@ -29,6 +29,7 @@
 //   probabilities leave the safe range are marked and redone by the exact kernel.
 #include <algorithm>
 #include <atomic>
+#include <cstdlib>
 
 #include "attn_common.h"
 
@@ -626,11 +627,26 @@ pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
         n_cu = v;
         n_cu_cached.store(v, std::memory_order_relaxed);
     }
-    // one workgroup per CU (its LDS admits no second one), or per tile if there are fewer
-    const int64_t grid = std::min<int64_t>((int64_t)p.n_tiles * p.dma_splits * p.hkv, n_cu);
-    hipLaunchKernelGGL(attn_dma128_kernel, dim3((unsigned)grid), dim3(kAttnThreads),
-                       kLdsBytes, st, p);
-    if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
+    // Two kernels do this job: eight waves of 32 columns (two waves per SIMD, the default)
+    // and four waves of 64 columns (one per SIMD).  PKV_ATTN_WAVES=4 in the environment
+    // selects the latter, for comparisons.
+    static std::atomic<int> waves{0};
+    int nw = waves.load(std::memory_order_relaxed);
+    if (nw == 0) {
+        const char* e = std::getenv("PKV_ATTN_WAVES");
+        nw = (e && e[0] == '4') ? 4 : 8;
+        waves.store(nw, std::memory_order_relaxed);
+    }
+    if (nw == 8) {
+        const pkv_status rc = launch_attn_w8_main(p, n_cu, st);
+        if (rc != PKV_OK) return rc;
+    } else {
+        // one workgroup per CU (its LDS admits no second one), or per tile if there are fewer
+        const int64_t grid = std::min<int64_t>((int64_t)p.n_tiles * p.dma_splits * p.hkv, n_cu);
+        hipLaunchKernelGGL(attn_dma128_kernel, dim3((unsigned)grid), dim3(kAttnThreads),
+                           kLdsBytes, st, p);
+        if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
+    }
     if (p.dma_splits > 1)
         hipLaunchKernelGGL(attn_merge_splits_kernel, dim3((unsigned)((int64_t)p.m * p.hq)),
                            dim3(D), 0, st, p);

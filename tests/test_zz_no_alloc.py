@@ -34,14 +34,17 @@ def test_static_scratch_entry_point_matches_the_workspace_one(gpu_device):
         assert 0 < need <= api.STATIC_SCRATCH_BYTES
         ws = torch.empty(need, dtype=torch.uint8, device=gpu_device)
         prior = torch.rand(n_ctx, dtype=torch.float32, device=gpu_device)
+        warm = prior.clone()
+        api.pkv_query_score_static(cfg, q, k, warm)     # first call on the device: address lookup
+        torch.cuda.synchronize()
         for accumulate in (False, True):
             a, b = prior.clone(), prior.clone()
-            torch.cuda.synchronize()
-            before = torch.cuda.memory_allocated(gpu_device)
             api.pkv_query_score(cfg, q, k, a, accumulate=accumulate, ws=ws)
+            torch.cuda.synchronize()
+            free_before = torch.cuda.mem_get_info(gpu_device)[0]   # device-wide, not torch's pool
             api.pkv_query_score_static(cfg, q, k, b, accumulate=accumulate)
             torch.cuda.synchronize()
-            assert torch.cuda.memory_allocated(gpu_device) == before
+            assert torch.cuda.mem_get_info(gpu_device)[0] == free_before
             assert torch.equal(a, b)
         want = O.query_score(q_h.astype(np.float64), k_h.astype(np.float64))
         got = b.double().cpu().numpy() - prior.double().cpu().numpy()
