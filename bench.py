@@ -43,7 +43,7 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # HBM bytes per pkv_sparse_row_attn launch (V^T pre-pass + main kernel), from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/hot_path_cfg3_hbm_traffic.txt
 # (counters cannot be read from inside this process; the figure is for that workload only)
-MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 1.969e9}
+MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 2.022e9}
 TRAFFIC_SOURCE = ("profiles/hot_path_cfg3_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / "
                   "WRITE_SIZE of `bench.py --profile-call sparse_row_attn`, not read live)")
 PEAK_F32_TFLOPS = 157.3
@@ -639,7 +639,7 @@ def main():
                      "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(cfg.name),
                      "traffic_source": TRAFFIC_SOURCE,
                      "flops_per_launch": flops, "avg_launch_s": t_attn,
-                     "launch": "pkv_sparse_row_attn = V^T pre-pass + attn_dma128_kernel + "
+                     "launch": "pkv_sparse_row_attn = V^T pre-pass + attn_w8_kernel + "
                                "repair pass, timed with events on the launch stream"},
         "breakdown": breakdown,
     }
