@@ -85,11 +85,11 @@ pkv_status pkv_query_score_lse(const pkv_layer_cfg* cfg, const void* q, const vo
 pkv_status pkv_topk_select(const float* score, int64_t n, int64_t k,
                            int32_t* idx_out, void* ws, size_t ws_bytes,
                            void* stream) {
-    (void)ws; (void)ws_bytes;
     if (n < 0 || n > kMaxTokens || k < 0 || k > n) return PKV_ERR_SHAPE;
     if (k == 0) return PKV_OK;
     if (!score || !idx_out) return PKV_ERR_NULL;
-    return launch_topk_select(score, n, k, idx_out, (hipStream_t)stream);
+    // the workspace is optional here: without it long vectors take a one-workgroup kernel
+    return launch_topk_select(score, n, k, idx_out, ws, ws ? ws_bytes : 0, (hipStream_t)stream);
 }
 
 pkv_status pkv_gather_qkv_proj_ex(const pkv_layer_cfg* cfg, const void* hidden,
@@ -291,6 +291,8 @@ size_t pkv_workspace_bytes(int which_call, const pkv_layer_cfg* cfg, int64_t n,
     switch (which_call) {
         case PKV_CALL_QUERY_SCORE:
             return align256(query_score_ws_bytes(*cfg, n, m));
+        case PKV_CALL_TOPK_SELECT:
+            return align256(topk_select_ws_bytes(n));
         case PKV_CALL_GATHER_QKV_PROJ:
             return align256(gather_qkv_proj_ws_bytes(*cfg, m));
         case PKV_CALL_SPARSE_ROW_ATTN:

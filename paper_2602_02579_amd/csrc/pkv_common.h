@@ -81,8 +81,9 @@ pkv_status launch_scatter_kv(const pkv_layer_cfg& cfg, const void* k_new,
                              void* k_cache, void* v_cache, int64_t m,
                              hipStream_t st);
 
+size_t topk_select_ws_bytes(int64_t n);
 pkv_status launch_topk_select(const float* score, int64_t n, int64_t k,
-                              int32_t* idx_out, hipStream_t st);
+                              int32_t* idx_out, void* ws, size_t ws_bytes, hipStream_t st);
 
 size_t query_score_ws_bytes(const pkv_layer_cfg& cfg, int64_t n_ctx, int64_t nq);
 pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,

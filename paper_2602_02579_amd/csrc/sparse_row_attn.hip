@@ -6,6 +6,10 @@
 //   out[i,h] = sum_{t <= row_pos[i]} softmax_t(q[i,h] . K[t,g(h)] * scale) V[t,g(h)]
 #include <algorithm>
 #include <atomic>
+#include <functional>
+#include <mutex>
+#include <queue>
+#include <vector>
 
 #include "attn_common.h"
 
@@ -464,11 +468,6 @@ size_t attn_flag_bytes(const pkv_layer_cfg& cfg, int64_t m) {
     const size_t b = ((size_t)ceil_div(m, bm) * cfg.n_kv_heads + 1 + cfg.n_kv_heads) * sizeof(int);
     return (b + 255) & ~(size_t)255;
 }
-
-// Key ranges per row tile for the pipelined kernel.  With fewer (kv head, row tile) pairs
-// than CUs - Stage I's 128 query rows make 16 - every pair is cut along the keys into up to
-// 16 ranges (at least 1024 keys each, multiples of 64) so that the jobs fill the CUs of a
-// 256-CU part in as few rounds per unit of work as possible; the jobs write normalised
 // partial results that a small kernel merges.
 constexpr int kMaxCtxRanges = 32;   // ranges per tile when a boundary is forced
 
@@ -480,34 +479,99 @@ constexpr int kMaxCtxRanges = 32;   // ranges per tile when a boundary is forced
 bool attn_plan_splits_at(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m, int64_t ctx_keys,
                          int* n_splits, int* split_len);
 
+// Estimated time (us) of the pipelined launch when every row tile's keys are cut into `sp`
+// ranges, for one layout of the row limits (the limits live on the device; the host weighs
+// two layouts): `spread` = rows in position order with limits evenly over the keys, so tile i
+// of T reaches (i + 1) / T of them; otherwise every tile reaches all keys.  The launch is one
+// workgroup per CU claiming jobs heaviest first, which the longest-processing-time rule
+// models; a job costs its 64-key steps plus a fixed set-up (pipeline fill, output; with ranges
+// also the fp32 partial result), fitted to measured launches of 640 to 6681 rows.
+double attn_launch_estimate(int64_t tiles, int hkv, int64_t steps_full, int sp, bool spread,
+                            int n_cu) {
+    const double us_per_step = 1.68, job_fixed = 4.0 + (sp > 1 ? 8.0 : 0.0);
+    const int64_t range_steps = (steps_full + sp - 1) / sp;
+    std::vector<double> jobs;
+    jobs.reserve((size_t)(tiles * sp * hkv));
+    for (int64_t i = 0; i < tiles; ++i) {
+        const int64_t reach = spread ? std::max<int64_t>(1, (i + 1) * steps_full / tiles)
+                                     : steps_full;
+        for (int s = 0; s < sp; ++s) {
+            const int64_t st = std::min<int64_t>(range_steps, reach - (int64_t)s * range_steps);
+            if (st <= 0) break;
+            for (int g = 0; g < hkv; ++g) jobs.push_back(st * us_per_step + job_fixed);
+        }
+    }
+    std::sort(jobs.begin(), jobs.end(), std::greater<double>());
+    std::priority_queue<double, std::vector<double>, std::greater<double>> cu;
+    for (int c = 0; c < n_cu; ++c) cu.push(0.0);
+    double end = 0.0;
+    for (double j : jobs) {
+        const double t = cu.top() + j;
+        cu.pop();
+        cu.push(t);
+        end = std::max(end, t);
+    }
+    return end;
+}
+
+// Key ranges per row tile for the pipelined kernel.  With few (kv head, row tile) pairs per
+// CU the launch ends when its longest job does - Stage I's 128 query rows make 16 jobs for
+// 256 CUs, an 8k context with 1702 rows 216 jobs whose longest is twice the mean - so the
+// keys of every tile are cut into up to 16 ranges (at least 2048 keys each, multiples of 64);
+// the jobs write normalised partial results that a small kernel merges.  The count minimises
+// the estimated launch time (the two layouts above, weighted by the row count) plus what the ranges cost: the
+// jobs write and the merge kernel reads the partial results a row has (about 2 TB/s, measured, plus
+// a launch).  Plans are remembered per problem size.
 void attn_plan_splits(const pkv_layer_cfg& cfg, int64_t n_keys, int64_t m, int* n_splits,
                       int* split_len) {
     const int bm = 256 / (cfg.n_q_heads / cfg.n_kv_heads);
-    const int64_t jobs = ceil_div(m, bm) * cfg.n_kv_heads;
+    const int64_t tiles = ceil_div(m, bm);
+    const int64_t jobs = tiles * cfg.n_kv_heads;
     *n_splits = 1;
     *split_len = (int)pad64(n_keys);
-    if (cfg.head_dim != 128 || jobs >= 256 || jobs <= 0) return;
-    // Estimated time of the launch in microseconds for sp ranges per tile: rounds of a
-    // 256-CU part over the ranges (1.4 us per 64-key step, a range 1/sp of the keys),
-    // plus what every extra range costs - its prologue on the CUs that run it (5 us) and
-    // its share of the merge, which writes and reads m * hq * D fp32 per range at about
-    // 5 TB/s.  The row limits are on the device, so two layouts are weighed equally: every
-    // tile full length (jobs * sp ranges, e.g. query rows only) and limits spread evenly
-    // over the keys (about jobs * (sp + 1) / 2 ranges that hold keys).
-    const int64_t most = std::min<int64_t>(16, n_keys / 1024);
-    const double t_full = 1.4 * (double)ceil_div(n_keys, 64);
-    const double per_range = 5.0 * (double)jobs / 256.0 +
-                             2.0 * (double)m * cfg.n_q_heads * cfg.head_dim * 4.0 / 5.0e6;
-    int64_t want = 1;
-    double best = 1e30;
-    for (int64_t sp = 1; sp <= most; ++sp) {
-        const double rounds = 0.5 * (double)(ceil_div(jobs * sp, 256) +
-                                             ceil_div(jobs * (sp + 1) / 2, 256));
-        const double cost = rounds / sp * t_full + (sp > 1 ? sp * per_range : 0.0);
-        if (cost < best - 1e-9) {
-            best = cost;
-            want = sp;
+    if (cfg.head_dim != 128 || jobs >= 1024 || jobs <= 0) return;
+    const int64_t most = std::min<int64_t>(16, n_keys / 2048);   // ranges of 2048 keys or more
+    if (most < 2) return;
+
+    struct Plan { int64_t n_keys, m; int hq, hkv, want; };
+    static std::mutex mu;
+    static std::vector<Plan> cache;
+    int64_t want = 0;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        for (const Plan& c : cache)
+            if (c.n_keys == n_keys && c.m == m && c.hq == cfg.n_q_heads && c.hkv == cfg.n_kv_heads)
+                want = c.want;
+    }
+    if (want == 0) {
+        const int n_cu = 256;
+        const int64_t steps_full = ceil_div(n_keys, 64);
+        const double out_elems = (double)m * cfg.n_q_heads * cfg.head_dim;
+        // a handful of rows are the user query, which sees the whole cache; thousands of rows
+        // are selected context rows, whose positions cannot help being spread
+        const double w_full = std::min(1.0, std::max(0.0, (768.0 - (double)m) / 640.0));
+        double best = 1e30;
+        for (int64_t sp = 1; sp <= most; ++sp) {
+            const double run =
+                (1.0 - w_full) * attn_launch_estimate(tiles, cfg.n_kv_heads, steps_full, (int)sp,
+                                                      true, n_cu) +
+                w_full * attn_launch_estimate(tiles, cfg.n_kv_heads, steps_full, (int)sp, false,
+                                              n_cu);
+            // partial results: a row has (sp + 1) / 2 (spread) or sp (full) of them, fp32, written
+            // by the jobs and read back by the merge, which also writes the output.  Measured
+            // against unsplit launches (6681 rows in 2 ranges, 3404 in 4, 1702 in 2) the whole
+            // detour moves at about 2 TB/s.
+            const double ranges = w_full * sp + (1.0 - w_full) * 0.5 * (sp + 1);
+            const double merge = sp == 1 ? 0.0
+                : 5.0 + (out_elems * 4.0 * ranges * 2.0 + out_elems * 2.0) / 2.0e6;
+            if (run + merge < best - 1e-9) {
+                best = run + merge;
+                want = sp;
+            }
         }
+        std::lock_guard<std::mutex> lock(mu);
+        if (cache.size() >= 64) cache.erase(cache.begin());
+        cache.push_back(Plan{n_keys, m, cfg.n_q_heads, cfg.n_kv_heads, (int)want});
     }
     if (want <= 1) return;
     const int64_t len = pad64(ceil_div(n_keys, want));

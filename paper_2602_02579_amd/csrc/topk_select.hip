@@ -267,13 +267,251 @@ __global__ __launch_bounds__(kThreads) void topk_bisect_kernel(
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Longer vectors (n > 24576) with a workspace: the same radix select spread over many
+// workgroups, so that the counting runs at the bandwidth of the whole chip instead of one
+// CU's.  A workgroup of 256 lanes owns 2048 consecutive scores (8 per lane, in registers).
+//   hist<0>  histogram of the top 11 key bits              -> hist0[2048]
+//   hist<1>  (bin0, rest0) from hist0; next 11 bits of the keys in bin0 -> hist1[2048]
+//   hist<2>  (bin1, rest1) from hist1; last 10 bits of the keys in (bin0, bin1) -> hist2[1024]
+//   count    (bin2, need) from hist2 gives tau; per workgroup (keys > tau, keys == tau)
+//   write    exclusive sums over the workgroups before mine give my output offset; equal
+//            keys are taken in index order until `need` of them are - the lower-index rule
+// Each kernel scans only the newest histogram: workgroup 0 leaves the (bin, rest) pair it
+// found in the workspace for the kernels behind it.  Histogram updates are integer
+// atomics, so the result does not depend on their order.
+// Workspace (uint32 words): hist0[2048] hist1[2048] hist2[1024] sel[8] counts[2 * n_wg].
+// ---------------------------------------------------------------------------
+constexpr int kSeg = 2048;          // scores per workgroup
+constexpr int kSegThreads = 256;
+constexpr int kHistWords = 2048 + 2048 + 1024;
+
+__global__ __launch_bounds__(256) void topk_ws_zero_kernel(uint32_t* __restrict__ ws) {
+    for (int i = threadIdx.x; i < kHistWords + 8; i += 256) ws[i] = 0u;
+}
+
+// The bin b (counted from the top) with count(bins > b) < rest <= count(bins >= b), and what
+// is left of rest inside it.  All 256 lanes call it; the result is block-uniform.
+__device__ __forceinline__ void topk_find_bin(const uint32_t* __restrict__ hist, int nbins,
+                                              uint32_t rest, uint32_t* bin_out,
+                                              uint32_t* rest_out) {
+    __shared__ uint32_t s_wsum[4];
+    __shared__ uint32_t s_res[2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = nbins / kSegThreads;          // 8 or 4
+    uint32_t c[8];
+    uint32_t mine = 0;
+    // lane t owns bins [nbins - (t + 1) per, nbins - t per): the top bins belong to lane 0
+    const int hi = nbins - tid * per;
+    for (int j = 0; j < per; ++j) {
+        c[j] = hist[hi - 1 - j];                  // descending
+        mine += c[j];
+    }
+    uint32_t inc = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += o;
+    }
+    if (lane == 63) s_wsum[wave] = inc;
+    __syncthreads();
+    uint32_t above = inc - mine;                  // keys in bins above mine
+    for (int w = 0; w < wave; ++w) above += s_wsum[w];
+    for (int j = 0; j < per; ++j) {
+        if (above < rest && rest <= above + c[j]) {
+            s_res[0] = (uint32_t)(hi - 1 - j);
+            s_res[1] = rest - above;
+        }
+        above += c[j];
+    }
+    __syncthreads();
+    *bin_out = s_res[0];
+    *rest_out = s_res[1];
+    __syncthreads();                              // s_res / s_wsum may be reused
+}
+
+__device__ __forceinline__ void topk_load_keys(const float* __restrict__ score, int n, int base,
+                                               bool aligned, uint32_t* key) {
+#pragma unroll
+    for (int j = 0; j < 8; j += 4) {
+        if (aligned && base + j + 3 < n) {
+            const float4 v = *reinterpret_cast<const float4*>(score + base + j);
+            key[j] = order_key(v.x);
+            key[j + 1] = order_key(v.y);
+            key[j + 2] = order_key(v.z);
+            key[j + 3] = order_key(v.w);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)   // indices >= n: key 0, below every float's key
+                key[j + e] = base + j + e < n ? order_key(score[base + j + e]) : 0u;
+        }
+    }
+}
+
+template <int PASS>
+__global__ __launch_bounds__(256) void topk_ws_hist_kernel(const float* __restrict__ score, int n,
+                                                           int k, uint32_t* __restrict__ ws,
+                                                           int aligned) {
+    __shared__ uint32_t s_hist[2048];
+    uint32_t* hist0 = ws;
+    uint32_t* hist1 = ws + 2048;
+    uint32_t* hist2 = ws + 4096;
+    uint32_t* sel = ws + kHistWords;
+    const int tid = threadIdx.x;
+    constexpr int nbins = PASS == 2 ? 1024 : 2048;
+    for (int i = tid; i < nbins; i += 256) s_hist[i] = 0u;
+    uint32_t prefix = 0;        // the key bits fixed so far, right-aligned
+    if (PASS == 1) {
+        uint32_t b, r;
+        topk_find_bin(hist0, 2048, (uint32_t)k, &b, &r);
+        if (blockIdx.x == 0 && tid == 0) { sel[0] = b; sel[1] = r; }
+        prefix = b;
+    } else if (PASS == 2) {
+        uint32_t b, r;
+        topk_find_bin(hist1, 2048, sel[1], &b, &r);
+        if (blockIdx.x == 0 && tid == 0) { sel[2] = b; sel[3] = r; }
+        prefix = (sel[0] << 11) | b;
+    } else {
+        __syncthreads();
+    }
+    uint32_t key[8];
+    const int base = blockIdx.x * kSeg + tid * 8;
+    topk_load_keys(score, n, base, aligned != 0, key);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (base + j >= n) continue;
+        if (PASS == 0) atomicAdd(&s_hist[key[j] >> 21], 1u);
+        else if (PASS == 1) { if ((key[j] >> 21) == prefix) atomicAdd(&s_hist[(key[j] >> 10) & 2047u], 1u); }
+        else { if ((key[j] >> 10) == prefix) atomicAdd(&s_hist[key[j] & 1023u], 1u); }
+    }
+    __syncthreads();
+    uint32_t* out = PASS == 0 ? hist0 : PASS == 1 ? hist1 : hist2;
+    for (int i = tid; i < nbins; i += 256)
+        if (s_hist[i]) atomicAdd(&out[i], s_hist[i]);
+}
+
+__global__ __launch_bounds__(256) void topk_ws_count_kernel(const float* __restrict__ score, int n,
+                                                            uint32_t* __restrict__ ws, int aligned) {
+    __shared__ uint32_t s_g[4], s_e[4];
+    uint32_t* hist2 = ws + 4096;
+    uint32_t* sel = ws + kHistWords;
+    uint32_t* counts = sel + 8;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t b, need;
+    topk_find_bin(hist2, 1024, sel[3], &b, &need);
+    if (blockIdx.x == 0 && tid == 0) { sel[4] = b; sel[5] = need; }
+    const uint32_t tau = (sel[0] << 21) | (sel[2] << 10) | b;
+    uint32_t key[8];
+    const int base = blockIdx.x * kSeg + tid * 8;
+    topk_load_keys(score, n, base, aligned != 0, key);
+    uint32_t gt = 0, eq = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        gt += key[j] > tau ? 1u : 0u;
+        eq += (key[j] == tau && base + j < n) ? 1u : 0u;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        gt += __shfl_xor(gt, o, 64);
+        eq += __shfl_xor(eq, o, 64);
+    }
+    if (lane == 0) { s_g[wave] = gt; s_e[wave] = eq; }
+    __syncthreads();
+    if (tid == 0) {
+        counts[2 * blockIdx.x] = s_g[0] + s_g[1] + s_g[2] + s_g[3];
+        counts[2 * blockIdx.x + 1] = s_e[0] + s_e[1] + s_e[2] + s_e[3];
+    }
+}
+
+__global__ __launch_bounds__(256) void topk_ws_write_kernel(const float* __restrict__ score, int n,
+                                                            const uint32_t* __restrict__ ws,
+                                                            int32_t* __restrict__ idx_out,
+                                                            int aligned) {
+    __shared__ uint32_t s_g[4], s_e[4];
+    const uint32_t* sel = ws + kHistWords;
+    const uint32_t* counts = sel + 8;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t tau = (sel[0] << 21) | (sel[2] << 10) | sel[4];
+    const uint32_t need = sel[5];
+    // keys > tau and keys == tau in the workgroups before mine
+    uint32_t gb = 0, eb = 0;
+    for (int w = tid; w < (int)blockIdx.x; w += 256) {
+        gb += counts[2 * w];
+        eb += counts[2 * w + 1];
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        gb += __shfl_xor(gb, o, 64);
+        eb += __shfl_xor(eb, o, 64);
+    }
+    if (lane == 0) { s_g[wave] = gb; s_e[wave] = eb; }
+    __syncthreads();
+    const uint32_t gt_wg = s_g[0] + s_g[1] + s_g[2] + s_g[3];
+    const uint32_t eq_wg = s_e[0] + s_e[1] + s_e[2] + s_e[3];
+    __syncthreads();
+    uint32_t key[8];
+    const int base = blockIdx.x * kSeg + tid * 8;
+    topk_load_keys(score, n, base, aligned != 0, key);
+    uint32_t my_gt = 0, my_eq = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        my_gt += key[j] > tau ? 1u : 0u;
+        my_eq += (key[j] == tau && base + j < n) ? 1u : 0u;
+    }
+    uint32_t in_gt = my_gt, in_eq = my_eq;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t og = __shfl_up(in_gt, d, 64), oe = __shfl_up(in_eq, d, 64);
+        if (lane >= d) { in_gt += og; in_eq += oe; }
+    }
+    if (lane == 63) { s_g[wave] = in_gt; s_e[wave] = in_eq; }
+    __syncthreads();
+    uint32_t gt_before = gt_wg + in_gt - my_gt, eq_before = eq_wg + in_eq - my_eq;
+    for (int w = 0; w < wave; ++w) {
+        gt_before += s_g[w];
+        eq_before += s_e[w];
+    }
+    // equal keys at lower indices are taken first, until `need` of them are
+    uint32_t out = gt_before + (eq_before < need ? eq_before : need);
+    uint32_t eq_seen = eq_before;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const bool is_eq = key[j] == tau && base + j < n;
+        const bool take = key[j] > tau || (is_eq && eq_seen < need);
+        if (take) idx_out[out++] = base + j;
+        eq_seen += is_eq ? 1u : 0u;
+    }
+}
+
 }  // namespace
 
+// Shortest vector that takes the many-workgroup kernels when a workspace is given: their six
+// launches cost a flat ~20 us, the one-workgroup register kernel 10 us at 4k scores, 16 us
+// at 16k, 29 us at 32k and 46 us at 64k.
+constexpr int64_t kWsMin = 24 * 1024 + 1;
+
+size_t topk_select_ws_bytes(int64_t n) {
+    if (n < kWsMin || n > ((int64_t)1 << 22)) return 0;   // other kernels, no scratch
+    return (size_t)(kHistWords + 8 + 2 * ceil_div(n, kSeg)) * sizeof(uint32_t);
+}
+
 pkv_status launch_topk_select(const float* score, int64_t n, int64_t k,
-                              int32_t* idx_out, hipStream_t st) {
+                              int32_t* idx_out, void* ws, size_t ws_bytes, hipStream_t st) {
     if (n == 0 || k == 0) return PKV_OK;
     // the register kernels read 16 bytes at a time
     const bool aligned = (reinterpret_cast<uintptr_t>(score) & 15) == 0;
+    const size_t need = topk_select_ws_bytes(n);
+    if (need && ws && ws_bytes >= need && (reinterpret_cast<uintptr_t>(ws) & 3) == 0) {
+        uint32_t* w = (uint32_t*)ws;
+        const dim3 grid((unsigned)ceil_div(n, kSeg)), block(kSegThreads);
+        const int al = aligned ? 1 : 0;
+        hipLaunchKernelGGL(topk_ws_zero_kernel, dim3(1), block, 0, st, w);
+        hipLaunchKernelGGL(topk_ws_hist_kernel<0>, grid, block, 0, st, score, (int)n, (int)k, w, al);
+        hipLaunchKernelGGL(topk_ws_hist_kernel<1>, grid, block, 0, st, score, (int)n, (int)k, w, al);
+        hipLaunchKernelGGL(topk_ws_hist_kernel<2>, grid, block, 0, st, score, (int)n, (int)k, w, al);
+        hipLaunchKernelGGL(topk_ws_count_kernel, grid, block, 0, st, score, (int)n, w, al);
+        hipLaunchKernelGGL(topk_ws_write_kernel, grid, block, 0, st, score, (int)n, w, idx_out, al);
+        return launch_status();
+    }
     // a round costs one vector compare-and-count per register key, so short vectors take
     // the instantiation with the fewest keys per lane that holds them
     if (aligned && n <= 8 * kThreads) {
@@ -296,6 +534,7 @@ pkv_status launch_topk_select(const float* score, int64_t n, int64_t k,
                            (int)n, (int)k, idx_out);
         return launch_status();
     }
+    // no (or too small a) workspace: one workgroup does it all
     hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kThreads), 0, st, score,
                        (int)n, (int)k, idx_out);
     return launch_status();

@@ -87,7 +87,7 @@ class CarriedRows:
                 api.pkv_glue_workspace_bytes(tdt, rows, hid, self.inter),
                 api.pkv_glue_workspace_bytes(tdt, rows, self.inter, hid))
         ws_bytes = max(ws_bytes, api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, self.lc, n, qn),
-                       ctx_ws)
+                       api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, self.lc, n, 0), ctx_ws)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
 
     # one decoder layer for the first ``cnt`` rows of the buffers, at positions ``rows``
@@ -131,7 +131,7 @@ class CarriedRows:
             api.pkv_rope_restore(self.lc, L["k_nope"], L["k_cache"][:self.n], None, 0)
             if li < ls:
                 self._layer(L, self.q_rows, self.qn, score=li > 0)
-        api.pkv_topk_select(self.score, self.k, self.rows)
+        api.pkv_topk_select(self.score, self.k, self.rows, ws=self.ws)
 
     def stage2(self, embed: torch.Tensor, layers: List[Dict[str, torch.Tensor]]) -> torch.Tensor:
         """The rows ``self.rows`` through every layer; returns their final hidden states

@@ -72,6 +72,7 @@ class SelectiveRecompute:
             api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, self.lc, n + qn, self.m),
             api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, self.lc, 0, self.m),
             api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, self.lc, 0, qn),
+            api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, self.lc, n, 0),
             256)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=device)
 
@@ -86,7 +87,7 @@ class SelectiveRecompute:
                             accumulate=accumulate, ws=self.ws)
 
     def select(self) -> None:
-        api.pkv_topk_select(self.score, self.k, self.rows)
+        api.pkv_topk_select(self.score, self.k, self.rows, ws=self.ws)
 
     # ---- Stage II --------------------------------------------------------
     def recompute_layer(self, L: Dict[str, torch.Tensor]) -> None:

@@ -161,6 +161,54 @@ def test_topk_ties_negative_values_and_zeros(gpu_device):
     assert np.array_equal(run_topk(s, 1500, gpu_device), O.topk_select(s, 1500))
 
 
+def run_topk_ws(score_t, k, device):
+    cfg = lcfg("bf16", 32, 8, 128, 4096)
+    n = score_t.shape[0]
+    need = api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, cfg, n, 0)
+    ws = torch.full((max(need, 256),), 0xAB, dtype=torch.uint8, device=device)   # dirty scratch
+    out = torch.full((max(k, 1),), -7, dtype=torch.int32, device=device)
+    api.pkv_topk_select(score_t, k, out, ws=ws)
+    return out[:k].cpu().numpy(), need
+
+
+@pytest.mark.parametrize("n,k", [(131072, 26214), (24577, 1), (32768, 6553), (65537, 65537), (100003, 99999),
+                                 (262144, 52428), (1 << 20, 1000), (300001, 150000)])
+def test_topk_long_vectors_with_a_workspace(gpu_device, n, k):
+    """Vectors beyond 65536 scores: the many-workgroup radix select (workspace given)
+    against the oracle and against the one-workgroup kernel (no workspace)."""
+    g = np.random.default_rng(n ^ k)
+    s = (g.random(n).astype(np.float32) ** 4) / n        # skewed, like attention scores
+    st = torch.from_numpy(s).to(gpu_device)
+    got, need = run_topk_ws(st, k, gpu_device)
+    assert need > 0
+    want = O.topk_select(s, k)
+    assert np.array_equal(got, want)
+    assert np.array_equal(run_topk(s, k, gpu_device), want)
+    # twice through the same (now used) workspace gives the same indices
+    got2, _ = run_topk_ws(st, k, gpu_device)
+    assert np.array_equal(got2, want)
+
+
+def test_topk_long_vectors_ties_signs_and_alignment(gpu_device):
+    g = np.random.default_rng(19)
+    n = 200001
+    s = g.integers(-3, 4, size=n).astype(np.float32)              # heavy ties, both signs
+    s[::11] = 0.0
+    s[5::11] = -0.0
+    st = torch.from_numpy(s).to(gpu_device)
+    for k in (1, 77777, 123456, n):
+        got, _ = run_topk_ws(st, k, gpu_device)
+        assert np.array_equal(got, O.topk_select(s, k))
+    got, _ = run_topk_ws(st[1:], 50000, gpu_device)               # pointer offset by 4 bytes
+    assert np.array_equal(got, O.topk_select(s[1:], 50000))
+    ones = torch.ones(70000, dtype=torch.float32, device=gpu_device)   # all equal
+    got, _ = run_topk_ws(ones, 12345, gpu_device)
+    assert np.array_equal(got, np.arange(12345))
+    cfg = lcfg("bf16", 32, 8, 128, 4096)
+    assert api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, cfg, 24576, 0) == 0
+    assert api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, cfg, (1 << 22) + 1, 0) == 0
+
+
 # ------------------------------------------------------------------ score
 
 @pytest.mark.parametrize("dtype,nq,n_ctx,hq,hkv,d", [
@@ -349,7 +397,7 @@ def test_sparse_row_attn_more_row_tiles_than_workgroups(gpu_device, hq, hkv, m, 
 @pytest.mark.parametrize("hq,hkv,m,n_keys,query_rows", [
     (32, 8, 128, 8192 + 128, True),      # Stage I: the query rows alone, 16 (head, tile) pairs
     (32, 8, 200, 8300, False),           # rows anywhere: some see only the first key range
-    (8, 2, 500, 5000, False), (40, 8, 70, 3333, False)])
+    (8, 2, 500, 5000, False), (40, 8, 70, 6666, False)])
 def test_sparse_row_attn_few_rows_split_over_keys(gpu_device, hq, hkv, m, n_keys, query_rows):
     """Fewer (kv head, row tile) pairs than CUs: the keys of a tile are cut into ranges
     that run as separate jobs and are merged (rows that end inside a range, rows that
@@ -368,8 +416,10 @@ def test_sparse_row_attn_few_rows_split_over_keys(gpu_device, hq, hkv, m, n_keys
                                        vc.astype(np.float64), pos, dtype=dtype)
     out = torch.empty((m, hq, d), dtype=torch.bfloat16, device=gpu_device)
     lse = torch.empty((m, hq), dtype=torch.float32, device=gpu_device)
-    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, m), 256),
-                     dtype=torch.uint8, device=gpu_device)
+    need = api.pkv_workspace_bytes(api.CALL_SPARSE_ROW_ATTN, cfg, n_keys, m)
+    # the launcher did plan ranges: the scratch holds fp32 partial results for two or more
+    assert need > hkv * d * (n_keys + 64) * 2 + 1.5 * m * hq * (d + 1) * 4
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=gpu_device)
     ws.fill_(0xff)
     args = (dev(q, dtype, gpu_device), dev(kc, dtype, gpu_device), dev(vc, dtype, gpu_device),
             torch.from_numpy(pos).to(gpu_device))
@@ -429,7 +479,7 @@ def test_sparse_row_attn_closed_forms(gpu_device):
         assert np.abs(got[:, h] - vc[0, h // 4]).max() <= 2e-2 * np.abs(vc[0]).max()
 
 
-@pytest.mark.parametrize("n_keys", [700, 3000])   # 3000: the keys of a tile run as two ranges
+@pytest.mark.parametrize("n_keys", [700, 4500])   # 4500: the keys of a tile run as two ranges
 def test_sparse_row_attn_scores_far_above_the_first_keys(gpu_device, n_keys):
     """Late keys whose scores exceed everything among a row's first 32 keys by
     hundreds of nats: the fixed-reference fast path of the head_dim-128 kernel

@@ -41,7 +41,8 @@ def test_host_only_entry_points():
     cfg = api.LayerCfg(32, 8, 128, 4096, 5e5, "bf16")
     assert api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, cfg, 32768, 128) % 256 == 0
     assert api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, cfg, 32768, 128) > 0
-    assert api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, cfg, 32768, 0) == 0
+    assert api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, cfg, 16384, 0) == 0
+    assert api.pkv_workspace_bytes(api.CALL_TOPK_SELECT, cfg, 131072, 0) > 0
     bad = api.LayerCfg(32, 7, 128, 4096, 5e5, "bf16")
     assert api.pkv_workspace_bytes(api.CALL_QUERY_SCORE, bad, 32768, 128) == 0
 
