@@ -35,6 +35,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 SOURCE_FLAGS = {
     "sparse_row_attn_dma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "sparse_row_attn_w8.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "query_score_dma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }
 
 
