@@ -302,7 +302,10 @@ def extras(device):
     todo = [("cfg3-shape r=0.1", c3.with_(ratio=0.1)), ("cfg3-shape r=0.4", c3.with_(ratio=0.4)),
             ("cfg2 8k r=0.2", synth.CONFIGS[2]), ("cfg5 128k r=0.2", synth.CONFIGS[5])]
     todo += [(f"cfg4 32 layers r={r}", c4.with_(ratio=r)) for r in (0.1, 0.2, 0.4)]
-    return [extra_workload(name, cfg, device, steps=2 if cfg.n_layers > 1 else 3)
+    # the first three or four passes after an idle spell run up to 10 % slower than the
+    # steady state, so the short single-layer workloads get more warm-up passes
+    return [extra_workload(name, cfg, device, steps=2 if cfg.n_layers > 1 else 10,
+                           warmup=1 if cfg.n_layers > 1 else 5)
             for name, cfg in todo]
 
 
@@ -501,7 +504,28 @@ def carried_model(cfg, device, n_layers, inter=14336, eps=1e-5, steps=3):
         else:
             glue[name]["TFLOP/s"] = round(work / t / 1e12, 2)
             glue[name]["frac"] = round(work / t / 1e12 / PEAK_BF16_TFLOPS, 4)
+    # the scoring work of one Stage I layer on the query rows, both ways: attention that
+    # also emits the context-only normaliser + one column-sum pass, against the two-pass
+    # score + plain attention
+    stage1 = None
+    if cr.fuse_stage1:
+        q1, a1 = cr.q[:qn], cr.attn[:qn]
+        kc, vc = L["k_cache"], L["v_cache"]
+
+        def fused():
+            api.pkv_sparse_row_attn_ctx_lse(lc, q1, kc, vc, cr.q_rows, a1, None, cr.lse_ctx, n,
+                                            ws=cr.ws)
+            api.pkv_query_score_lse(lc, q1, kc[:n], cr.lse_ctx, None, cr.score,
+                                    accumulate=False, ws=cr.ws)
+
+        def two_calls():
+            api.pkv_query_score(lc, q1, kc[:n], cr.score, accumulate=False, ws=cr.ws)
+            api.pkv_sparse_row_attn(lc, q1, kc, vc, cr.q_rows, a1, None, ws=cr.ws)
+        stage1 = {"fused_us": round(time_calls(fused, 5) * 1e6, 1),
+                  "score_then_attention_us": round(time_calls(two_calls, 5) * 1e6, 1),
+                  "what": "query-row attention + score of one scoring layer (128 rows, 32k keys)"}
     return {"layers": n_layers, "n_score_layers": cfg.n_score_layers, "mlp_width": inter,
+            "stage1_scoring_layer": stage1,
             "rows_stage2": m, "rows_stage1": qn, "ms_per_pass": round(per_pass * 1e3, 3),
             "ms_per_layer_stage2_est": round(sum(v["us"] for v in glue.values()) * 1e-3, 3),
             "recomputed_tokens_per_s": round(m * n_layers / per_pass, 1),
