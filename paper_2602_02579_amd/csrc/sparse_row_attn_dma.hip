@@ -515,14 +515,18 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
             }
         }
     }
-    if (p.dma_splits > 1) {
-        // normalised partial result of this key range; rows that see none of it leave
-        // garbage that the merge never reads
+    // A row whose keys all lie in the first range has its whole result in that range's job:
+    // it is written as the final output there and never merged.  Every other row leaves a
+    // normalised fp32 partial result per range it reaches.
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            if (!valid[cb]) continue;
+    for (int cb = 0; cb < 2; ++cb) {
+        if (!valid[cb]) continue;
+        const int pos = min(p.row_pos[row[cb]], p.n_keys - 1);
+        const bool direct = p.dma_splits == 1 || pos < p.dma_split_len;
+        const float inv = 1.f / l_tot[cb];
+        if (!direct) {
+            if (pos < kb) continue;   // the row sees nothing of this range
             const int64_t colg = ((int64_t)split * p.m + row[cb]) * p.hq + head[cb];
-            const float inv = 1.f / l_tot[cb];
             float* op = p.part_o + colg * D + 4 * hh;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -534,14 +538,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
                     *reinterpret_cast<f32x4*>(op + db * 32 + r4 * 8) = v;
                 }
             if (hh == 0) p.part_lse[colg] = m_run[cb] * p.scale + logf(l_tot[cb]);
+            continue;
         }
-        continue;
-    }
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        if (!valid[cb]) continue;
+        if (split != 0) continue;
         const int64_t colg = (int64_t)row[cb] * p.hq + head[cb];
-        const float inv = 1.f / l_tot[cb];
         bf16_t* op = p.out + colg * D + 4 * hh;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -555,7 +555,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
         if (hh == 0) {
             const float lse = m_run[cb] * p.scale + logf(l_tot[cb]);
             if (p.lse) p.lse[colg] = lse;
-            // unsplit launches are only asked for this when every key is a context key
+            // asked for only when every key the row sees is a context key: unsplit launches
+            // whose keys are all context keys, and first-range rows (a range boundary lies
+            // at the end of the context)
             if (p.lse_ctx) p.lse_ctx[colg] = lse;
         }
     }
@@ -564,28 +566,39 @@ __global__ __launch_bounds__(kAttnThreads) void attn_dma128_kernel(AttnParams p)
 
 // Merge of the key ranges of a split launch: out = sum_s w_s O_s / sum_s w_s with
 // w_s = exp(lse_s - max lse), over the ranges that begin at or below the row's limit.
-// One workgroup of D threads per (row, head); tiles marked for the exact kernel are left
-// to it.
-__global__ __launch_bounds__(D) void attn_merge_splits_kernel(AttnParams p) {
-    const int64_t col = blockIdx.x;           // row * hq + head
+// 32 lanes of four output elements per (row, head), eight of them per workgroup.  Rows whose
+// keys all lie in the first range were written by that range's job; tiles marked for the
+// exact kernel are left to it.
+constexpr int kMergeCols = 8;
+static_assert(D == 128, "one (row, head) is 32 lanes of four floats");
+__global__ __launch_bounds__(32 * kMergeCols) void attn_merge_splits_kernel(AttnParams p) {
+    const int64_t col = (int64_t)blockIdx.x * kMergeCols + (threadIdx.x >> 5);   // row * hq + head
+    if (col >= (int64_t)p.m * p.hq) return;
     const int row = (int)(col / p.hq), head = (int)(col % p.hq);
     if (p.flags[(row / p.bm) * p.hkv + head / p.group]) return;
     const int limit = min(p.row_pos[row], p.n_keys - 1);
     const int n_s = limit / p.dma_split_len + 1;   // <= dma_splits
-    const int d = threadIdx.x;
+    if (n_s == 1) return;
+    const int l = threadIdx.x & 31;
     float mx = -INFINITY;
     for (int sp = 0; sp < n_s; ++sp)
         mx = fmaxf(mx, p.part_lse[((int64_t)sp * p.m + row) * p.hq + head]);
-    float acc = 0.f, wsum = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float wsum = 0.f;
     for (int sp = 0; sp < n_s; ++sp) {
         const int64_t c = ((int64_t)sp * p.m + row) * p.hq + head;
         const float w = __expf(p.part_lse[c] - mx);
+        const f32x4 o = *reinterpret_cast<const f32x4*>(p.part_o + c * D + 4 * l);
         wsum += w;
-        acc += w * p.part_o[c * D + d];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += w * o[e];
     }
-    p.out[col * D + d] = (bf16_t)(acc / wsum);
-    if (p.lse && d == 0) p.lse[col] = mx + logf(wsum);
-    if (p.lse_ctx && d == 0) {
+    bf16x4 v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(acc[e] / wsum);
+    *reinterpret_cast<bf16x4*>(p.out + col * D + 4 * l) = v;
+    if (p.lse && l == 0) p.lse[col] = mx + logf(wsum);
+    if (p.lse_ctx && l == 0) {
         // the ranges that lie below ctx_keys (a range boundary): the same sum, cut there
         const int n_c = min(n_s, p.ctx_keys / p.dma_split_len);
         float mc = -INFINITY;
@@ -648,8 +661,9 @@ pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
         if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
     }
     if (p.dma_splits > 1)
-        hipLaunchKernelGGL(attn_merge_splits_kernel, dim3((unsigned)((int64_t)p.m * p.hq)),
-                           dim3(D), 0, st, p);
+        hipLaunchKernelGGL(attn_merge_splits_kernel,
+                           dim3((unsigned)(((int64_t)p.m * p.hq + kMergeCols - 1) / kMergeCols)),
+                           dim3(32 * kMergeCols), 0, st, p);
     return launch_status();
 }
 

@@ -443,22 +443,27 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
     }
     if (valid) {
         const float inv = 1.f / l_tot;
-        if (p.dma_splits > 1) {
-            // normalised partial result of this key range (rows that see none of it leave
-            // garbage that the merge never reads)
-            const int64_t colg = ((int64_t)split * p.m + row) * p.hq + head;
-            float* op = p.part_o + colg * D + 4 * hh;
+        // A row whose keys all lie in the first range has its whole result in that range's
+        // job: it is written as the final output there and never merged.  Every other row
+        // leaves a normalised fp32 partial result per range it reaches.
+        const int pos = min(p.row_pos[row], p.n_keys - 1);
+        const bool direct = p.dma_splits == 1 || pos < p.dma_split_len;
+        if (!direct) {
+            if (pos >= kb) {   // else the row sees nothing of this range
+                const int64_t colg = ((int64_t)split * p.m + row) * p.hq + head;
+                float* op = p.part_o + colg * D + 4 * hh;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    f32x4 v;
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        f32x4 v;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = o_acc[db][4 * r4 + e] * inv;
-                    *reinterpret_cast<f32x4*>(op + db * 32 + r4 * 8) = v;
-                }
-            if (hh == 0) p.part_lse[colg] = m_run * p.scale + logf(l_tot);
-        } else {
+                        for (int e = 0; e < 4; ++e) v[e] = o_acc[db][4 * r4 + e] * inv;
+                        *reinterpret_cast<f32x4*>(op + db * 32 + r4 * 8) = v;
+                    }
+                if (hh == 0) p.part_lse[colg] = m_run * p.scale + logf(l_tot);
+            }
+        } else if (split == 0) {
             const int64_t colg = (int64_t)row * p.hq + head;
             bf16_t* op = p.out + colg * D + 4 * hh;
 #pragma unroll
@@ -473,7 +478,9 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
             if (hh == 0) {
                 const float lse = m_run * p.scale + logf(l_tot);
                 if (p.lse) p.lse[colg] = lse;
-                // unsplit launches are only asked for this when every key is a context key
+                // asked for only when every key the row sees is a context key: unsplit
+                // launches whose keys are all context keys, and first-range rows (a range
+                // boundary lies at the end of the context)
                 if (p.lse_ctx) p.lse_ctx[colg] = lse;
             }
         }
