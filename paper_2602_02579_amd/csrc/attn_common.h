@@ -12,6 +12,9 @@ struct AttnParams {
     const bf16_t* q;
     const bf16_t* k;
     const bf16_t* vt;        // [hkv, D, n_pad], zero beyond n_keys
+    const bf16_t* v;         // [n_keys, hkv, D] as the cache holds it, or nullptr: when set, the
+                             // eight-wave pipelined kernel reads it and vt is filled only if a
+                             // tile gets marked for the exact kernel
     const int32_t* row_pos;  // [m] or nullptr when fixed_limit >= 0
     bf16_t* out;             // [m, hq, D]
     float* lse;              // [m, hq] or nullptr
@@ -41,5 +44,11 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st);
 // its main kernel with eight waves of 32 columns per workgroup (sparse_row_attn_w8.hip)
 pkv_status launch_attn_w8_main(const AttnParams& p, int n_cu, hipStream_t st);
+// Where launch_attn_dma128's main kernel can take the values from: 1 = only from a V^T copy
+// made by a pre-pass (the four-wave kernel, PKV_ATTN_WAVES=4, or PKV_ATTN_VT=1 in the
+// environment), 0 = always from the cache as it is (PKV_ATTN_VT=0), -1 = either, the caller
+// chooses by size.  The environment settings exist for comparisons and tests (PKV_ATTN_VT is
+// read at every call, PKV_ATTN_WAVES once).
+int attn_dma128_v_source();
 
 }  // namespace pkv

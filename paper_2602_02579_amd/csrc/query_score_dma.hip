@@ -3,8 +3,9 @@
 // (Paper: Algorithm 1 first stage, alpha_l = Softmax(Q_s K'^T / sqrt(d_k)) over the
 // context keys; Sec. 4.2 mean over the user-query tokens; Appendix E mean over heads.)
 //
-// A workgroup of 4 waves owns 256 columns (query token, head of one kv group) and
-// one split of the key range.  The columns are the ROWS of the MFMA tile here,
+// A workgroup of NW = 8 waves (two per SIMD, so that the softmax arithmetic of one wave
+// runs under the matrix instructions and waits of the other) owns 256 columns (query token,
+// head of one kv group) and one split of the key range; a wave owns 256 / NW of them.  The columns are the ROWS of the MFMA tile here,
 //     S [32 cols x 32 keys] = Q (A operand, registers) x K^T (B operand, LDS)
 // so that a lane holds one key (l % 32) of a 32-key block and, in its 16
 // accumulator registers, 16 of the 32 columns.  Sums over keys (pass 1: the
@@ -56,9 +57,16 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int PASS>
-__global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
+constexpr int kScoreWaves = 8;
+
+template <int PASS, int NW>
+__global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
+    static_assert(NW == 8, "256 columns over 8 waves of 32 (the operand ring below assumes it)");
+    constexpr int NCB = 8 / NW;      // 32-column blocks of a wave
+    constexpr int FILLS = 16 / NW;   // fill instructions of a wave per tile (4 key rows each)
     extern __shared__ __align__(16) unsigned char smem[];
+    // pass 2 with 8 waves: waves w and w + 4 add their key sums before they leave the CU
+    __shared__ float s_pair[2][4][kTile];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -78,10 +86,10 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
     const float c2 = p.scale_log2;
 
     // ---- Q as A operands: row l32 of column block cb ------------------------------------
-    bf16x8 qreg[2][KC];
+    bf16x8 qreg[NCB][KC];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int col = cblk * 256 + wave * 64 + cb * 32 + l32;
+    for (int cb = 0; cb < NCB; ++cb) {
+        const int col = cblk * 256 + wave * (32 * NCB) + cb * 32 + l32;
         const bool valid = col < ncol_g;
         const int qi = valid ? col / p.group : 0;
         const int h = g * p.group + (valid ? col % p.group : 0);
@@ -98,21 +106,21 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
     }
     // accumulator register r of column block cb belongs to this column:
     auto acc_col = [&](int cb, int r) {
-        return cblk * 256 + wave * 64 + cb * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
+        return cblk * 256 + wave * (32 * NCB) + cb * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
     };
 
-    // ---- global -> LDS: wave w fills key rows 16w .. 16w+15 of every stage ------------------
+    // ---- global -> LDS: wave w fills key rows (64/NW) w .. (64/NW) (w+1) - 1 of every stage --
     const uint32_t k_row_bytes = (uint32_t)p.hkv * D * 2;
-    int krow[4];
-    uint32_t kchunk16[4];
+    int krow[FILLS];
+    uint32_t kchunk16[FILLS];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = 16 * wave + 4 * i + (lane >> 4);
+    for (int i = 0; i < FILLS; ++i) {
+        const int r = 4 * FILLS * wave + 4 * i + (lane >> 4);
         krow[i] = r;
         kchunk16[i] = (uint32_t)(((lane & 15) ^ (r & 15)) * 16);
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds0 + wave * 16 * 256);
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds0 + wave * 4 * FILLS * 256);
     const bf16_t* const k_head = p.k + (int64_t)g * D;
     // tile T of the split (clamped to its last tile) into ring slot T % NS
     auto dma_tile = [&](int T) {
@@ -122,7 +130,7 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
         const bf16_t* gb = k_head + (int64_t)t0 * p.hkv * D;
         const int last = p.n_ctx - 1 - t0;   // rows past the context re-read its last key
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < FILLS; ++i)
             dma16(gb, (uint32_t)min(krow[i], last) * k_row_bytes + kchunk16[i],
                   lds_wave + slot * kStage + i * 1024);
     };
@@ -134,21 +142,27 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) kaddr[kc] = a0 ^ (kc << 5);
     }
-    bf16x8 kf[2][KC];
-    auto load_kf = [&](int T, int kb, int kc) {
-        kf[kb][kc] = *reinterpret_cast<const bf16x8*>(smem + (T % NS) * kStage + kb * 32 * 256 +
-                                                      kaddr[kc]);
+    // The B operands of a tile are used once each (16 MFMAs: contraction chunk kc = i / 2,
+    // key block kb = i % 2), so they pass through a ring of 8 registers quadruples, read from
+    // LDS kLook MFMAs before their use.
+    constexpr int kLook = 6;
+    bf16x8 kq[8];
+    auto load_op = [&](int T, int i, int slot) {
+        kq[slot] = *reinterpret_cast<const bf16x8*>(smem + (T % NS) * kStage + (i & 1) * 32 * 256 +
+                                                    kaddr[i >> 1]);
     };
 
     // ---- per-pass state --------------------------------------------------------------------
-    float norm[2][16];    // pass 2: log2-domain normaliser of my 32 columns (inf = no column)
-    float msc[2][16];     // pass 1: reference maximum of my columns over this lane's keys, times c2
-    float lsum[2][16];    //         sum of exp2(s c2 - msc) over this lane's keys, up to the
-    float tsum[2][16];    //         previous tile; the previous tile's own sum (not yet added)
+    float norm[NCB][16];  // pass 2: log2-domain normaliser of my columns (inf = no column)
+    float msc[NCB][16];   // pass 1: reference maximum of my columns over this lane's keys, times c2
+    float lsum[NCB][16];  //         sum of exp2(s c2 - msc) over this lane's keys, up to the
+    float tsum[NCB][16];  //         previous tile; the previous tile's own sum (not yet added)
     float ksum[2] = {0.f, 0.f};   // pass 2: this tile's two keys, summed over my columns
+    float pend[2] = {0.f, 0.f};   // pass 2, 8 waves: the previous tile's sums, not yet stored
+    int pend_t0 = -1;
     constexpr float kGrow = 1.0e24f;
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int col = acc_col(cb, r);
@@ -164,37 +178,30 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
             }
         }
 
-    f32x16 s_a[2][2], s_b[2][2];   // S of one 64-key tile: [column block][key block]
+    f32x16 s_a[NCB][2], s_b[NCB][2];   // S of one 64-key tile: [column block][key block]
 
     // ---- prologue --------------------------------------------------------------------------
 #pragma unroll
     for (int T = 0; T < NS - 1; ++T) dma_tile(T);
-    wait_vm<4 * (NS - 2)>();   // tile 0
+    wait_vm<FILLS * (NS - 2)>();   // tile 0
     __syncthreads();
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-        load_kf(0, 0, kc);
-        load_kf(0, 1, kc);
-    }
     {
         const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                           0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-            for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-                    s_a[cb][kb] = mfma32(qreg[cb][kc], kf[kb][kc], kc == 0 ? z : s_a[cb][kb]);
+        for (int i = 0; i < 16; ++i) {   // S(0), operands through the ring two at a time
+            if ((i & 1) == 0) {
+                load_op(0, i, i & 7);
+                load_op(0, i + 1, (i + 1) & 7);
+            }
+            s_a[0][i & 1] = mfma32(qreg[0][i >> 1], kq[i & 7], i < 2 ? z : s_a[0][i & 1]);
+        }
     }
-    wait_vm<4 * (NS - 3)>();   // tile 1
+    wait_vm<FILLS * (NS - 3)>();   // tile 1
     __syncthreads();
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-        load_kf(1, 0, kc);
-        load_kf(1, 1, kc);
-    }
-    wait_vm<4 * (NS - 4)>();   // tile 2
+    for (int i = 0; i < kLook; ++i) load_op(1, i, i);
+    wait_vm<FILLS * (NS - 4)>();   // tile 2 (the look-ahead of tile 0's last MFMAs reads it)
     __syncthreads();
 
     // exponents of the two keys of column (CB, R) of the tile in S
@@ -215,8 +222,10 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
         if (PASS == 1) {                                                                 \
             lsum[CB][R] += tsum[CB][R];   /* the previous tile's sum */                  \
             tsum[CB][R] = pe0_ + pe1_;                                                   \
-            tmax_ = fmaxf(tmax_, tsum[CB][R]);                                           \
-            asm volatile("" : "+v"(lsum[CB][R]), "+v"(tsum[CB][R]), "+v"(tmax_));        \
+            /* one instruction: fmaxf would first quiet a signalling NaN (a second  */   \
+            /* v_max); a NaN sum needs no rescue and the hardware maximum drops it  */   \
+            asm volatile("v_max_f32 %0, %0, %1" : "+v"(tmax_) : "v"(tsum[CB][R]));       \
+            asm volatile("" : "+v"(lsum[CB][R]), "+v"(tsum[CB][R]));                     \
         } else {                                                                         \
             ksum[0] += pe0_;                                                             \
             ksum[1] += pe1_;                                                             \
@@ -224,8 +233,9 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
         }                                                                                \
     }
 
-    // One tile: CUR = S(T) is turned into sums while NXT = S(T+1) is formed from the
-    // operands in kf, which are replaced by those of tile T+2 as they fall free.
+    // One tile: CUR = S(T) is turned into sums while NXT = S(T+1) is formed; the operand of
+    // MFMA i + kLook (of tile T+1, or of tile T+2 behind the tile's end) is requested after
+    // MFMA i.
 #define PKV_SCORE_TILE(CUR, NXT, T, RAGGED)                                                      \
     {                                                                                    \
         const int t0_ = key_begin + (T) * kTile;                                         \
@@ -234,23 +244,20 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
         float xa_, xb_, pe0_ = 0.f, pe1_ = 0.f;                                          \
         PKV_SCORE_PREP(CUR, 0, 0, RAGGED)                                                \
         _Pragma("unroll") for (int kc = 0; kc < KC; ++kc) {                              \
-            _Pragma("unroll") for (int q4 = 0; q4 < 4; ++q4) {                           \
+            _Pragma("unroll") for (int q4 = 0; q4 < 2; ++q4) {                           \
                 const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,               \
                                    0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};              \
-                const int cb_ = q4 >> 1, kb_ = q4 & 1;                                   \
-                NXT[cb_][kb_] = mfma32(qreg[cb_][kc], kf[kb_][kc],                       \
-                                       kc == 0 ? z_ : NXT[cb_][kb_]);                    \
-                if (q4 == 3) {                                                           \
-                    load_kf((T) + 2, 0, kc);                                             \
-                    load_kf((T) + 2, 1, kc);                                             \
-                }                                                                        \
+                const int i_ = kc * 2 + q4;                                              \
+                NXT[0][q4] = mfma32(qreg[0][kc], kq[i_ & 7], kc == 0 ? z_ : NXT[0][q4]); \
+                if (i_ + kLook < 16) load_op((T) + 1, i_ + kLook, (i_ + kLook) & 7);     \
+                else load_op((T) + 2, i_ + kLook - 16, (i_ + kLook) & 7);                \
                 /* softmax step: column (scb_, sr_), keys of both key blocks.  The    */ \
                 /* exponents were formed one step earlier and the results are added   */ \
                 /* one step later, so nothing waits on the transcendental unit.       */ \
-                const int step_ = kc * 4 + q4, scb_ = step_ >> 4, sr_ = step_ & 15;      \
+                const int step_ = i_, scb_ = step_ >> 4, sr_ = step_ & 15;               \
                 const float e0_ = __builtin_amdgcn_exp2f(xa_);                           \
                 const float e1_ = __builtin_amdgcn_exp2f(xb_);                           \
-                if (step_ < 31) {                                                        \
+                if (step_ < 16 * NCB - 1) {                                              \
                     const int ncb_ = (step_ + 1) >> 4, nr_ = (step_ + 1) & 15;           \
                     PKV_SCORE_PREP(CUR, ncb_, nr_, RAGGED)                               \
                 }                                                                        \
@@ -265,13 +272,13 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
                 __builtin_amdgcn_sched_barrier(0);                                       \
             }                                                                            \
         }                                                                                \
-        PKV_SCORE_ADD(1, 15)                                                             \
+        PKV_SCORE_ADD(NCB - 1, 15)                                                       \
         if (PASS == 1) {                                                                 \
             /* an infinite sum shows here too; a NaN does not, and needs no rescue */  \
             if (__builtin_expect(__any(!(tmax_ < kGrow)), 0)) {                          \
                 /* some sum left the safe range: raise the references to this tile's  */ \
                 /* maxima where they are larger, rescale, form the tile's sums again  */ \
-                _Pragma("unroll") for (int cb = 0; cb < 2; ++cb)                         \
+                _Pragma("unroll") for (int cb = 0; cb < NCB; ++cb)                       \
                 _Pragma("unroll") for (int r = 0; r < 16; ++r) {                         \
                     float x0_ = CUR[cb][0][r], x1_ = CUR[cb][1][r];                      \
                     if (t0_ + l32 >= key_end) x0_ = -INFINITY;                           \
@@ -289,24 +296,48 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
             }                                                                            \
         } else {                                                                         \
             /* the other half of the wave holds the other 16 columns of each block */    \
+            float tot_[2];                                                               \
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                           \
                 const auto sw_ = __builtin_amdgcn_permlane32_swap(                       \
                     __float_as_uint(ksum[kb]), __float_as_uint(ksum[kb]), false, false); \
-                const int key_ = t0_ + kb * 32 + l32;                                    \
-                if (hh == 0 && key_ < key_end)                                           \
-                    p.part_score[((int64_t)(g * p.n_cblk + cblk) * 4 + wave) * p.n_ctx + key_] = \
-                        __uint_as_float(sw_[0]) + __uint_as_float(sw_[1]);               \
+                tot_[kb] = __uint_as_float(sw_[0]) + __uint_as_float(sw_[1]);            \
                 ksum[kb] = 0.f;                                                          \
             }                                                                            \
+            float* const part_ =                                                         \
+                p.part_score + ((int64_t)(g * p.n_cblk + cblk) * 4 + (wave & 3)) * p.n_ctx; \
+            if (NW == 4) {                                                               \
+                _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                       \
+                    const int key_ = t0_ + kb * 32 + l32;                                \
+                    if (hh == 0 && key_ < key_end) part_[key_] = tot_[kb];               \
+                }                                                                        \
+            } else if (wave >= 4) {                                                      \
+                /* read by wave - 4 after this tile's barrier, written again two tiles on */ \
+                if (hh == 0) {                                                           \
+                    s_pair[(T) & 1][wave - 4][l32] = tot_[0];                            \
+                    s_pair[(T) & 1][wave - 4][32 + l32] = tot_[1];                       \
+                }                                                                        \
+            } else {                                                                     \
+                /* the previous tile: the partner's sums are in LDS since its barrier */ \
+                if (pend_t0 >= 0) {                                                      \
+                    _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                   \
+                        const int key_ = pend_t0 + kb * 32 + l32;                        \
+                        if (hh == 0 && key_ < key_end)                                   \
+                            part_[key_] = pend[kb] + s_pair[((T) - 1) & 1][wave][kb * 32 + l32]; \
+                    }                                                                    \
+                }                                                                        \
+                pend[0] = tot_[0];                                                       \
+                pend[1] = tot_[1];                                                       \
+                pend_t0 = t0_;                                                           \
+            }                                                                            \
         }                                                                                \
-        wait_vm<8>();   /* tile T+3 has landed (loads and the stores above complete in */ \
-        __syncthreads(); /* order among themselves; 8 leaves room for the two youngest) */ \
+        wait_vm<2 * FILLS>();   /* tile T+3 has landed (loads and the stores above complete */ \
+        __syncthreads(); /* in order among themselves; this leaves room for the two youngest) */ \
     }
 
     // the reference of pass 1 starts as the maximum over the first tile (per lane)
     if (PASS == 1) {
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 float x0 = s_a[cb][0][r], x1 = s_a[cb][1][r];
@@ -333,6 +364,16 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
         else PKV_SCORE_TILE(s_a, s_b, T, false)
     }
     wait_vm<0>();   // nothing may still be writing LDS when the workgroup retires
+    if (PASS == 2 && NW == 8 && wave < 4 && pend_t0 >= 0) {
+        // the last tile's sums (its barrier has passed: the partner's are in LDS)
+        float* const part = p.part_score + ((int64_t)(g * p.n_cblk + cblk) * 4 + wave) * p.n_ctx;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const int key = pend_t0 + kb * 32 + l32;
+            if (hh == 0 && key < key_end)
+                part[key] = pend[kb] + s_pair[(n_iter - 1) & 1][wave][kb * 32 + l32];
+        }
+    }
 #undef PKV_SCORE_TILE
 #undef PKV_SCORE_PREP
 #undef PKV_SCORE_ADD
@@ -345,14 +386,15 @@ __global__ __launch_bounds__(256) void score_dma128_kernel(ScoreParams p) {
         // consecutive columns, one j) spread over all banks
         float2* ex = reinterpret_cast<float2*>(smem);
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int c = wave * 64 + cb * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
+                const int c = wave * (32 * NCB) + cb * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
                 ex[l32 * 256 + ((c + l32) & 255)] =
                     make_float2(msc[cb][r], lsum[cb][r] + tsum[cb][r]);
             }
         __syncthreads();
+        if (tid >= 256) return;   // one thread per column from here on
         const int c = tid;
         float m = -INFINITY, l = 0.f;   // running (reference * c2, sum) over the lanes with keys
         for (int j = 0; j < 32; ++j) {
@@ -403,10 +445,10 @@ bool score_dma128_supported(const pkv_layer_cfg& cfg, int64_t n_ctx, int64_t nq)
 pkv_status launch_score_dma128(int pass, const ScoreParams& p, hipStream_t st) {
     static std::atomic<bool> configured{false};   // set twice at worst: the calls are idempotent
     if (!configured.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_dma128_kernel<1>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_dma128_kernel<1, kScoreWaves>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(score_dma128_kernel<2>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(score_dma128_kernel<2, kScoreWaves>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
@@ -416,11 +458,11 @@ pkv_status launch_score_dma128(int pass, const ScoreParams& p, hipStream_t st) {
         return PKV_ERR_NULL;
     const int64_t grid = (int64_t)p.n_cblk * p.n_splits * p.hkv;
     if (pass == 1)
-        hipLaunchKernelGGL(score_dma128_kernel<1>, dim3((unsigned)grid), dim3(256), kLdsBytes,
-                           st, p);
+        hipLaunchKernelGGL((score_dma128_kernel<1, kScoreWaves>), dim3((unsigned)grid),
+                           dim3(64 * kScoreWaves), kLdsBytes, st, p);
     else
-        hipLaunchKernelGGL(score_dma128_kernel<2>, dim3((unsigned)grid), dim3(256), kLdsBytes,
-                           st, p);
+        hipLaunchKernelGGL((score_dma128_kernel<2, kScoreWaves>), dim3((unsigned)grid),
+                           dim3(64 * kScoreWaves), kLdsBytes, st, p);
     return launch_status();
 }
 

@@ -409,17 +409,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
 
 // V [n_keys, hkv, D] -> V^T [hkv, D, n_pad], zero for keys >= n_keys.
 // 64 x 64 tiles through LDS; reads and writes are both 16-byte, coalesced.
-__global__ __launch_bounds__(256) void transpose_v_kernel(
-    const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int n_keys, int n_pad,
-    int hkv, int d, int* zero, int n_zero) {
-    __shared__ bf16_t tile[64][64 + 2];
-    // this pre-pass also clears what the attention kernel expects at zero: the count of
-    // tiles marked for the repair pass, the work-queue counters and, when the keys are
-    // split, the marks themselves
-    if (zero && blockIdx.x == 0 && blockIdx.y == 0)
-        for (int i = threadIdx.x; i < n_zero; i += 256) zero[i] = 0;
-    const int t0 = blockIdx.x * 64;
-    const int c0 = blockIdx.y * 64;  // column in the flattened [hkv * D] axis
+__device__ __forceinline__ void transpose_v_tile(const bf16_t* __restrict__ v,
+                                                 bf16_t* __restrict__ vt, int n_keys, int n_pad,
+                                                 int hkv, int d, int bx, int by,
+                                                 bf16_t (*tile)[64 + 2]) {
+    const int t0 = bx * 64;
+    const int c0 = by * 64;  // column in the flattened [hkv * D] axis
     const int tid = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -446,6 +441,39 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(
         // flattened column c0 + dd = g * D + d  ->  row of V^T
         *reinterpret_cast<bf16x8*>(vt + (int64_t)(c0 + dd) * n_pad + t0 + tch * 8) = val;
     }
+}
+
+__global__ __launch_bounds__(256) void transpose_v_kernel(
+    const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int n_keys, int n_pad,
+    int hkv, int d, int* zero, int n_zero) {
+    __shared__ bf16_t tile[64][64 + 2];
+    // this pre-pass also clears what the attention kernel expects at zero: the count of
+    // tiles marked for the repair pass, the work-queue counters and, when the keys are
+    // split, the marks themselves
+    if (zero && blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = threadIdx.x; i < n_zero; i += 256) zero[i] = 0;
+    transpose_v_tile(v, vt, n_keys, n_pad, hkv, d, blockIdx.x, blockIdx.y, tile);
+}
+
+// The pipelined kernel that reads the values as the cache holds them needs no V^T; the
+// exact kernel that redoes the tiles it marked does.  This launch between the two makes the
+// copy only when something was marked (*marked != 0): normally every workgroup leaves at
+// once.  A fixed grid walks the tiles.
+__global__ __launch_bounds__(256) void transpose_v_if_marked_kernel(
+    const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int n_keys, int n_pad,
+    int hkv, int d, const int* marked) {
+    __shared__ bf16_t tile[64][64 + 2];
+    if (*marked == 0) return;   // the same for every thread of the launch
+    const int nx = n_pad / 64, ny = hkv * d / 64;
+    for (int t = blockIdx.x; t < nx * ny; t += gridDim.x) {
+        transpose_v_tile(v, vt, n_keys, n_pad, hkv, d, t % nx, t / nx, tile);
+        __syncthreads();   // the tile buffer is reused
+    }
+}
+
+// What the pipelined kernel expects at zero when no V^T pre-pass runs before it.
+__global__ __launch_bounds__(256) void attn_clear_kernel(int* zero, int n_zero) {
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < n_zero; i += gridDim.x * 256) zero[i] = 0;
 }
 
 bool mfma_attn_supported(const pkv_layer_cfg& cfg) {
@@ -710,15 +738,40 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         // cleared by the pre-pass: marked count + queue counters, and the marks when split
         int* zero = d == 128 ? (n_splits > 1 ? ints : ints + n_flags) : nullptr;
         const int n_zero = (n_splits > 1 ? n_flags : 0) + 1 + cfg.n_kv_heads;
-        hipLaunchKernelGGL(transpose_v_kernel,
-                           dim3((unsigned)(n_pad / 64), (unsigned)(cfg.n_kv_heads * d / 64)),
-                           dim3(256), 0, st, (const bf16_t*)v_cache, vt, (int)n_keys, n_pad,
-                           cfg.n_kv_heads, d, zero, n_zero);
+        // The eight-wave pipelined kernel can transpose the values on their way out of LDS
+        // instead of reading a V^T copy made here.  Its loop is then ~2.5 % slower (half as
+        // many bytes per LDS instruction), the copy costs its bytes at ~5.5 TB/s plus a launch,
+        // and doing without it costs two small launches: the copy is skipped when that is the
+        // cheaper side, which it is for the user-query rows and for short launches over long
+        // caches (measured: 128 rows over 32k keys 110 -> 94 us, 1766 rows 477 -> 468 us,
+        // 6681 rows 1490 -> 1501 us, 883 rows over 4k keys 77 -> 81 us).
+        bool nat_v = false;
+        if (d == 128) {
+            const int src = attn_dma128_v_source();
+            if (src < 0) {
+                const int bm = 256 / (cfg.n_q_heads / cfg.n_kv_heads);
+                const double copy_us = 3.0 + (double)n_pad * cfg.n_kv_heads * d * 4.0 / 5.5e6;
+                const double main_us = 1.68 * (double)ceil_div(m, bm) * cfg.n_kv_heads *
+                                       (double)(n_pad / 64) * (m > 768 ? 0.5 : 1.0) / 256.0;
+                nat_v = copy_us - 6.0 > 0.025 * main_us;
+            } else {
+                nat_v = src == 0;
+            }
+        }
+        if (nat_v)
+            hipLaunchKernelGGL(attn_clear_kernel, dim3((unsigned)std::min(64, (n_zero + 255) / 256)),
+                               dim3(256), 0, st, zero, n_zero);
+        else
+            hipLaunchKernelGGL(transpose_v_kernel,
+                               dim3((unsigned)(n_pad / 64), (unsigned)(cfg.n_kv_heads * d / 64)),
+                               dim3(256), 0, st, (const bf16_t*)v_cache, vt, (int)n_keys, n_pad,
+                               cfg.n_kv_heads, d, zero, n_zero);
         if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
         AttnParams p = {};
         p.q = (const bf16_t*)q;
         p.k = (const bf16_t*)k_cache;
         p.vt = vt;
+        p.v = nat_v ? (const bf16_t*)v_cache : nullptr;
         p.row_pos = row_pos;
         p.out = (bf16_t*)out;
         p.lse = lse_out;
@@ -751,6 +804,13 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         }
         const pkv_status rc = launch_attn_dma128(p, st);
         if (rc != PKV_OK) return rc;
+        if (nat_v) {
+            const int n_vt_tiles = (n_pad / 64) * (cfg.n_kv_heads * d / 64);
+            hipLaunchKernelGGL(transpose_v_if_marked_kernel, dim3((unsigned)std::min(n_vt_tiles, 2048)),
+                               dim3(256), 0, st, (const bf16_t*)v_cache, vt, (int)n_keys, n_pad,
+                               cfg.n_kv_heads, d, p.flags + p.n_tiles * p.hkv);
+            if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
+        }
         return launch_attn_mfma<128, true>(p, st);
     }
     const int block = d <= 64 ? 64 : (d <= 128 ? 128 : 256);

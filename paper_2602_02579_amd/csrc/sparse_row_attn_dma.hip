@@ -613,10 +613,32 @@ __global__ __launch_bounds__(32 * kMergeCols) void attn_merge_splits_kernel(Attn
 
 }  // namespace
 
+namespace {
+// 8 (default) or 4 waves per workgroup, from PKV_ATTN_WAVES, read once
+int attn_main_waves() {
+    static std::atomic<int> waves{0};
+    int nw = waves.load(std::memory_order_relaxed);
+    if (nw == 0) {
+        const char* e = std::getenv("PKV_ATTN_WAVES");
+        nw = (e && e[0] == '4') ? 4 : 8;
+        waves.store(nw, std::memory_order_relaxed);
+    }
+    return nw;
+}
+}  // namespace
+
+int attn_dma128_v_source() {
+    if (attn_main_waves() != 8) return 1;
+    // read at every call, so that one process can run both sources side by side
+    const char* e = std::getenv("PKV_ATTN_VT");
+    return !e ? -1 : (e[0] == '1' ? 1 : (e[0] == '0' ? 0 : -1));
+}
+
 pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
     // every workgroup reports through p.flags; the operands must all be there
     if (!p.q || !p.k || !p.vt || !p.row_pos || !p.out || !p.flags || !p.queue)
         return PKV_ERR_NULL;
+    if (p.v && attn_main_waves() != 8) return PKV_ERR_UNSUPPORTED;
     if (p.dma_splits < 1 || p.dma_split_len < kBN || p.dma_split_len % kBN ||
         (int64_t)p.dma_splits * p.dma_split_len < p.n_keys)
         return PKV_ERR_SHAPE;
@@ -643,13 +665,7 @@ pkv_status launch_attn_dma128(const AttnParams& p, hipStream_t st) {
     // Two kernels do this job: eight waves of 32 columns (two waves per SIMD, the default)
     // and four waves of 64 columns (one per SIMD).  PKV_ATTN_WAVES=4 in the environment
     // selects the latter, for comparisons.
-    static std::atomic<int> waves{0};
-    int nw = waves.load(std::memory_order_relaxed);
-    if (nw == 0) {
-        const char* e = std::getenv("PKV_ATTN_WAVES");
-        nw = (e && e[0] == '4') ? 4 : 8;
-        waves.store(nw, std::memory_order_relaxed);
-    }
+    const int nw = attn_main_waves();
     if (nw == 8) {
         const pkv_status rc = launch_attn_w8_main(p, n_cu, st);
         if (rc != PKV_OK) return rc;

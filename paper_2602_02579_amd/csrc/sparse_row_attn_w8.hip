@@ -61,6 +61,20 @@ __device__ __forceinline__ void mfma32_acc(bf16x8 a, bf16x8 b, f32x16& c) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
 }
 
+// Four 16-bit elements per lane through the transposing LDS read: within each group of 16
+// lanes, lane i receives as element e the element i % 4 of what lane 4 e + i / 4 addressed.
+// With lane 4 e + j addressing V[key + e][d0 + 4 j .. d0 + 4 j + 3] of a tile stored key-major,
+// lane i ends up with V[key .. key + 3][d0 + i]: an A-operand fragment of V^T.
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x4 lds_read_tr(const unsigned char* ptr) {
+    const i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) i16x4*)ptr);
+    return __builtin_bit_cast(bf16x4, v);
+}
+
+// kNatV: the values are read from the cache as it is (key-major) and transposed on their
+// way out of LDS; otherwise from a V^T copy made by a pre-pass.
+template <bool kNatV>
 __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int s_red[NW];
@@ -170,10 +184,13 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
     // K stage: key row r at byte r*256, 16-byte chunk c at c ^ (r & 15).  V^T stage: row d at
     // byte d*128, chunk c at c ^ ((d >> 1) & 7).  A wave instruction fills 1 KB; wave w owns K
     // rows [8w, 8w+8) and V^T rows [16w, 16w+16) of every tile: two instructions each.
+    // Key-major V stage (kNatV): key row r at byte r*256, chunk c at c ^ (4 (r & 3)), so that
+    // the four rows x 64 bytes a half wave reads in one transposing instruction cover all 64
+    // banks once; wave w owns rows [8w, 8w+8).
     const uint32_t lds_k = (uint32_t)(uintptr_t)smem;
     const uint32_t lds_v = lds_k + NS * kStageK;
     const uint32_t k_row_bytes = (uint32_t)p.hkv * D * 2;
-    uint32_t voff_k[2], voff_v[2], kofs_last[2];
+    uint32_t voff_k[2], voff_v[2], kofs_last[2], vofs_last[2];
     {
         const int last = (n_keys_job - 1) % kBN;   // last row of the (possibly ragged) last tile
 #pragma unroll
@@ -182,14 +199,23 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
             const uint32_t chunk = (uint32_t)(((lane & 15) ^ (r & 15)) * 16);
             voff_k[i] = (uint32_t)r * k_row_bytes + chunk;
             kofs_last[i] = (uint32_t)min(r, last) * k_row_bytes + chunk;
-            const int d = 16 * wave + 8 * i + (lane >> 3);
-            voff_v[i] = (uint32_t)d * (uint32_t)p.n_pad * 2u + (((lane & 7) ^ ((d >> 1) & 7)) * 16);
+            if (kNatV) {
+                const uint32_t vchunk = (uint32_t)(((lane & 15) ^ (4 * (r & 3))) * 16);
+                voff_v[i] = (uint32_t)r * k_row_bytes + vchunk;
+                vofs_last[i] = (uint32_t)min(r, last) * k_row_bytes + vchunk;
+            } else {
+                const int d = 16 * wave + 8 * i + (lane >> 3);
+                voff_v[i] =
+                    (uint32_t)d * (uint32_t)p.n_pad * 2u + (((lane & 7) ^ ((d >> 1) & 7)) * 16);
+                vofs_last[i] = voff_v[i];
+            }
         }
     }
     const uint32_t lds_k_wave = __builtin_amdgcn_readfirstlane(lds_k + wave * 8 * 256);
     const uint32_t lds_v_wave = __builtin_amdgcn_readfirstlane(lds_v + wave * 16 * 128);
     const bf16_t* const k_head = p.k + ((int64_t)kb * p.hkv + g) * D;
-    const bf16_t* const v_head = p.vt + (int64_t)g * D * p.n_pad + kb;
+    const bf16_t* const v_head = kNatV ? p.v + ((int64_t)kb * p.hkv + g) * D
+                                       : p.vt + (int64_t)g * D * p.n_pad + kb;
 
     // K tile T / V^T tile T (clamped to the last tile) into their ring slots, both instructions
 #define W8_DMA_K(T)                                                                      \
@@ -203,26 +229,32 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
     }
 #define W8_DMA_V(T)                                                                      \
     {                                                                                    \
-        const bf16_t* gb_ = v_head + min((T), n_iter - 1) * kBN;                         \
+        const int t_ = min((T), n_iter - 1);                                             \
+        const bf16_t* gb_ = kNatV ? v_head + (int64_t)t_ * kBN * p.hkv * D               \
+                                  : v_head + t_ * kBN;                                   \
+        const bool full_ = t_ * kBN + kBN <= n_keys_job;                                 \
         _Pragma("unroll") for (int i = 0; i < 2; ++i)                                    \
-            dma16(gb_, voff_v[i], lds_v_wave + ((T) & 3) * kStageV + i * 1024);          \
+            dma16(gb_, full_ ? voff_v[i] : vofs_last[i],                                 \
+                  lds_v_wave + ((T) & 3) * kStageV + i * 1024);                          \
     }
     // the four fill instructions of a tile body (K tile J+4, V^T tile J+2), one pair per
     // sub-step, prepared once per tile
     const bf16_t* gbk_;
     const bf16_t* gbv_;
-    bool k_full_;
+    bool k_full_, v_full_;
 #define W8_DMA_PREP(J)                                                                   \
     {                                                                                    \
         const int tk_ = min((J) + 4, n_iter - 1);                                        \
         gbk_ = k_head + (int64_t)tk_ * kBN * p.hkv * D;                                  \
         k_full_ = tk_ * kBN + kBN <= n_keys_job;   /* wave-uniform */                    \
-        gbv_ = v_head + min((J) + 2, n_iter - 1) * kBN;                                  \
+        const int tv_ = min((J) + 2, n_iter - 1);                                        \
+        gbv_ = kNatV ? v_head + (int64_t)tv_ * kBN * p.hkv * D : v_head + tv_ * kBN;     \
+        v_full_ = tv_ * kBN + kBN <= n_keys_job;                                         \
     }
 #define W8_DMA_ONE_K(I, SDK)                                                             \
     dma16(gbk_, k_full_ ? voff_k[I] : kofs_last[I], lds_k_wave + (SDK) * kStageK + (I) * 1024);
 #define W8_DMA_ONE_V(I, SDV)                                                             \
-    dma16(gbv_, voff_v[I], lds_v_wave + (SDV) * kStageV + (I) * 1024);
+    dma16(gbv_, v_full_ ? voff_v[I] : vofs_last[I], lds_v_wave + (SDV) * kStageV + (I) * 1024);
 
     // ---- LDS -> register operand addresses (bytes inside a stage) -----------------------------
     // A-row i of a 32-key block reads key swap_bits23(i) of that block, so that accumulator
@@ -233,9 +265,19 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
         const uint32_t a0 = prow * 256 + (((prow & 15) ^ hh) * 16);
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) kaddr[kc] = a0 ^ (kc << 5);
-        const uint32_t v0 = l32 * 128 + ((((l32 >> 1) & 7) ^ hh) * 16);
+        if (kNatV) {
+            // vaddr[db]: the 8 bytes this lane addresses for the d-block db of a 16-key chunk
+            // (row 8 hh + e of the chunk, d = 32 db + 16 gh + 4 j .. + 3)
+            const int e = (lane >> 2) & 3, j = lane & 3, gh = (lane >> 4) & 1;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) vaddr[q] = v0 ^ (q << 5);
+            for (int db = 0; db < 4; ++db)
+                vaddr[db] = (uint32_t)((8 * hh + e) * 256 +
+                                       (((db ^ e) * 4 + gh * 2 + (j >> 1)) * 16) + (j & 1) * 8);
+        } else {
+            const uint32_t v0 = l32 * 128 + ((((l32 >> 1) & 7) ^ hh) * 16);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) vaddr[q] = v0 ^ (q << 5);
+        }
     }
     const float c2 = p.scale_log2;
 
@@ -259,8 +301,15 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
     ka[KCI] = *reinterpret_cast<const bf16x8*>(                                          \
         smem + (ST) * kStageK + (H) * 32 * 256 + kaddr[KCI]);
 #define W8_LOAD_VA1(ST, H, KK, DBI)                                                      \
-    va[KK][DBI] = *reinterpret_cast<const bf16x8*>(                                      \
-        smem + NS * kStageK + (ST) * kStageV + (DBI) * 32 * 128 + vaddr[2 * (H) + (KK)]);
+    if (kNatV) {                                                                         \
+        const unsigned char* a_ = smem + NS * kStageK + (ST) * kStageV +                 \
+                                  (32 * (H) + 16 * (KK)) * 256 + vaddr[DBI];             \
+        const bf16x4 lo_ = lds_read_tr(a_), hi_ = lds_read_tr(a_ + 4 * 256);             \
+        va[KK][DBI] = __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7);         \
+    } else {                                                                             \
+        va[KK][DBI] = *reinterpret_cast<const bf16x8*>(                                  \
+            smem + NS * kStageK + (ST) * kStageV + (DBI) * 32 * 128 + vaddr[2 * (H) + (KK)]); \
+    }
 
     // exponent of element R of score buffer S whose first key is T0
 #define W8_SM_PREP(S, R, T0, MASK)                                                       \
@@ -491,9 +540,12 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
 }  // namespace
 
 pkv_status launch_attn_w8_main(const AttnParams& p, int n_cu, hipStream_t st) {
-    static std::atomic<bool> configured{false};   // set twice at worst: the call is idempotent
+    static std::atomic<bool> configured{false};   // set twice at worst: the calls are idempotent
     if (!configured.load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_w8_kernel),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_w8_kernel<false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes) != hipSuccess ||
+            hipFuncSetAttribute(reinterpret_cast<const void*>(attn_w8_kernel<true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kLdsBytes) != hipSuccess)
             return PKV_ERR_LAUNCH;
@@ -501,7 +553,12 @@ pkv_status launch_attn_w8_main(const AttnParams& p, int n_cu, hipStream_t st) {
     }
     // one workgroup per CU (its LDS admits no second one), or per job if there are fewer
     const int64_t grid = std::min<int64_t>((int64_t)p.n_tiles * p.dma_splits * p.hkv, n_cu);
-    hipLaunchKernelGGL(attn_w8_kernel, dim3((unsigned)grid), dim3(kThreads), kLdsBytes, st, p);
+    if (p.v)   // the values as the cache holds them; p.vt is then only the repair pass's
+        hipLaunchKernelGGL(attn_w8_kernel<true>, dim3((unsigned)grid), dim3(kThreads), kLdsBytes,
+                           st, p);
+    else
+        hipLaunchKernelGGL(attn_w8_kernel<false>, dim3((unsigned)grid), dim3(kThreads),
+                           kLdsBytes, st, p);
     return launch_status();
 }
 

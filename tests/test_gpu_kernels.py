@@ -331,7 +331,7 @@ def test_gather_qkv_proj_matches_oracle(gpu_device, dtype, m, hq, hkv, d, hid, t
     ("bf16", 333, 2048 + 61, 32, 8, 128), ("bf16", 70, 300, 4, 4, 64),
     ("bf16", 100, 777, 10, 2, 128), ("bf16", 1, 1, 32, 8, 128),
     ("bf16", 300, 500, 4, 1, 128), ("bf16", 150, 321, 6, 3, 128), ("bf16", 90, 200, 48, 3, 128)])
-def test_sparse_row_attn_matches_oracle(gpu_device, dtype, m, n_keys, hq, hkv, d):
+def test_sparse_row_attn_matches_oracle(gpu_device, dtype, m, n_keys, hq, hkv, d, v_source):
     cfg = lcfg(dtype, hq, hkv, d)
     g = np.random.default_rng(19)
     q = rnd(20, (m, hq, d), dtype, 1.2)
@@ -360,7 +360,7 @@ def test_sparse_row_attn_matches_oracle(gpu_device, dtype, m, n_keys, hq, hkv, d
 
 
 @pytest.mark.parametrize("hq,hkv,m,n_keys", [(16, 16, 4400, 600), (32, 8, 2200, 900)])
-def test_sparse_row_attn_more_row_tiles_than_workgroups(gpu_device, hq, hkv, m, n_keys):
+def test_sparse_row_attn_more_row_tiles_than_workgroups(gpu_device, hq, hkv, m, n_keys, v_source):
     """More (kv head, row tile) pairs than the launch has workgroups, so that every
     workgroup claims several and the heads run out at different times; rows in no
     particular order, so that the tiles differ in cost.  Who claims a tile must not
@@ -398,7 +398,7 @@ def test_sparse_row_attn_more_row_tiles_than_workgroups(gpu_device, hq, hkv, m, 
     (32, 8, 128, 8192 + 128, True),      # Stage I: the query rows alone, 16 (head, tile) pairs
     (32, 8, 200, 8300, False),           # rows anywhere: some see only the first key range
     (8, 2, 500, 5000, False), (40, 8, 70, 6666, False)])
-def test_sparse_row_attn_few_rows_split_over_keys(gpu_device, hq, hkv, m, n_keys, query_rows):
+def test_sparse_row_attn_few_rows_split_over_keys(gpu_device, hq, hkv, m, n_keys, query_rows, v_source):
     """Fewer (kv head, row tile) pairs than CUs: the keys of a tile are cut into ranges
     that run as separate jobs and are merged (rows that end inside a range, rows that
     never reach a range, a ragged last range)."""
@@ -432,7 +432,7 @@ def test_sparse_row_attn_few_rows_split_over_keys(gpu_device, hq, hkv, m, n_keys
 
 
 @pytest.mark.parametrize("seed", range(12))
-def test_sparse_row_attn_random_shapes(gpu_device, seed):
+def test_sparse_row_attn_random_shapes(gpu_device, seed, v_source):
     """Seeded random geometry, row count, cache length and row limits (head_dim 128,
     bf16): whatever tiling, key ranges and claim order the launcher picks, the rows match."""
     g = np.random.default_rng(1000 + seed)
@@ -480,7 +480,7 @@ def test_sparse_row_attn_closed_forms(gpu_device):
 
 
 @pytest.mark.parametrize("n_keys", [700, 4500])   # 4500: the keys of a tile run as two ranges
-def test_sparse_row_attn_scores_far_above_the_first_keys(gpu_device, n_keys):
+def test_sparse_row_attn_scores_far_above_the_first_keys(gpu_device, n_keys, v_source):
     """Late keys whose scores exceed everything among a row's first 32 keys by
     hundreds of nats: the fixed-reference fast path of the head_dim-128 kernel
     cannot represent them and must hand the tile to the exact kernel."""

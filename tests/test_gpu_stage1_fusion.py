@@ -64,13 +64,13 @@ def ctx_lse_case(gpu_device, n_ctx, n_tail, pos, seed, q_scale=1.2, spike=None):
     return q, kc, host(lse_ctx), want_ctx
 
 
-def test_context_lse_of_the_query_rows(gpu_device):
+def test_context_lse_of_the_query_rows(gpu_device, v_source):
     """The first stage's shape: the query rows behind a 4096-key context."""
     n_ctx, qn = 4096, 128
     ctx_lse_case(gpu_device, n_ctx, qn, np.arange(n_ctx, n_ctx + qn), 700)
 
 
-def test_context_lse_with_rows_inside_the_context_and_a_ragged_tail(gpu_device):
+def test_context_lse_with_rows_inside_the_context_and_a_ragged_tail(gpu_device, v_source):
     n_ctx, tail = 1536, 37
     g = np.random.default_rng(5)
     pos = np.sort(np.concatenate([g.choice(n_ctx, 90, replace=False),
@@ -79,11 +79,11 @@ def test_context_lse_with_rows_inside_the_context_and_a_ragged_tail(gpu_device):
     ctx_lse_case(gpu_device, n_ctx, tail, pos, 710)
 
 
-def test_context_lse_when_every_key_is_a_context_key(gpu_device):
+def test_context_lse_when_every_key_is_a_context_key(gpu_device, v_source):
     ctx_lse_case(gpu_device, 2048, 0, np.arange(2048 - 70, 2048), 720)
 
 
-def test_context_lse_through_the_exact_kernel(gpu_device):
+def test_context_lse_through_the_exact_kernel(gpu_device, v_source):
     """A key far above the reference of its column marks the tile; the exact kernel
     redoes it and must cut its running sums at the context boundary too."""
     n_ctx, qn = 2048, 64
