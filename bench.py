@@ -43,9 +43,9 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # HBM bytes per pkv_sparse_row_attn launch (V^T pre-pass + main kernel), from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/hot_path_cfg3_hbm_traffic.txt
 # (counters cannot be read from inside this process; the figure is for that workload only)
-MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 2.022e9}
+MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 2.051e9}
 TRAFFIC_SOURCE = ("profiles/hot_path_cfg3_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / "
-                  "WRITE_SIZE of `bench.py --profile-call sparse_row_attn`, not read live)")
+                  "WRITE_SIZE runs of this program, commands in the file; not read live)")
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
@@ -257,6 +257,29 @@ def timed_passes(sr, layers, steps):
     finally:
         pipeline.api.pkv_sparse_row_attn = orig_attn
     return elapsed, float(np.mean([s.elapsed_time(e) for s, e in ev])) * 1e-3
+
+
+def graph_replay_ms(sr, layers, steps):
+    """Milliseconds per pass when one pass, captured into a graph, is replayed."""
+    cur = torch.cuda.current_stream()
+    side = torch.cuda.Stream()          # default priority
+    side.wait_stream(cur)
+    with torch.cuda.stream(side):
+        sr.run(layers)
+    cur.wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sr.run(layers)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    del graph
+    return round(ms, 4)
 
 
 def extra_workload(name, cfg, device, steps=3, warmup=1, seed=77):
@@ -588,11 +611,17 @@ def main():
             "sparse_row_attn": lambda: api.pkv_sparse_row_attn(
                 sr.lc, sr.q, L0["k_cache"], L0["v_cache"], sr.rows, sr.out, sr.lse, ws=sr.ws),
         }[args.profile_call]
+        one()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for _ in range(args.reps):
             one()
+        e1.record()
         torch.cuda.synchronize()
         print(json.dumps({"profiled_call": args.profile_call, "reps": args.reps,
-                          "workload": cfg.name}))
+                          "workload": cfg.name,
+                          "us_per_call": round(e0.elapsed_time(e1) * 1e3 / args.reps, 1)}))
         return
 
     # ---- timed region: exactly K steps; the dominant kernel (step 5) is
@@ -677,6 +706,13 @@ def main():
     torch.cuda.synchronize()
     result["ms_per_step_fused_cache_update"] = round(
         (time.perf_counter() - t0) / args.steps * 1e3, 4)
+    if not args.no_extras:
+        # the same two passes replayed from a captured graph: what is left of the launch
+        # gaps between the small kernels at the head of a pass (outside `value`, whose timed
+        # region carries the events of the roofline and is launched call by call)
+        result["ms_per_step_graph_replay"] = graph_replay_ms(sr, layers, args.steps)
+        result["ms_per_step_fused_cache_update_graph_replay"] = graph_replay_ms(
+            sr_f, layers, args.steps)
     del sr_f
     if not args.no_extras and cfg.dtype == "bf16":
         result["diagnostics"] = diagnostics_report(device, layers[0], plants, sr)
