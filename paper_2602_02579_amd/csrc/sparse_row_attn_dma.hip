@@ -580,15 +580,20 @@ __global__ __launch_bounds__(32 * kMergeCols) void attn_merge_splits_kernel(Attn
     const int n_s = limit / p.dma_split_len + 1;   // <= dma_splits
     if (n_s == 1) return;
     const int l = threadIdx.x & 31;
+    // (unrolled by four so that the loads of four ranges are in flight together: with up to
+    // 32 ranges per row the loop is otherwise a chain of memory latencies)
+    const float* const lse_col = p.part_lse + (int64_t)row * p.hq + head;
+    const float* const o_col = p.part_o + ((int64_t)row * p.hq + head) * D + 4 * l;
+    const int64_t lse_step = (int64_t)p.m * p.hq, o_step = lse_step * D;
     float mx = -INFINITY;
-    for (int sp = 0; sp < n_s; ++sp)
-        mx = fmaxf(mx, p.part_lse[((int64_t)sp * p.m + row) * p.hq + head]);
+#pragma unroll 4
+    for (int sp = 0; sp < n_s; ++sp) mx = fmaxf(mx, lse_col[sp * lse_step]);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float wsum = 0.f;
+#pragma unroll 4
     for (int sp = 0; sp < n_s; ++sp) {
-        const int64_t c = ((int64_t)sp * p.m + row) * p.hq + head;
-        const float w = __expf(p.part_lse[c] - mx);
-        const f32x4 o = *reinterpret_cast<const f32x4*>(p.part_o + c * D + 4 * l);
+        const float w = __expf(lse_col[sp * lse_step] - mx);
+        const f32x4 o = *reinterpret_cast<const f32x4*>(o_col + sp * o_step);
         wsum += w;
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[e] += w * o[e];
