@@ -324,6 +324,33 @@ def test_gather_qkv_proj_matches_oracle(gpu_device, dtype, m, hq, hkv, d, hid, t
     assert torch.equal(q3, qo)
 
 
+@pytest.mark.parametrize("hid", [1024, 1152])
+def test_gather_qkv_proj_more_tiles_than_cus(gpu_device, hid):
+    """2900 rows x (32 + 2 x 8) heads = 288 tiles of 256 x 256: more than one round of the 256
+    CUs, a ragged last token tile, and the XCD-aware tile order over more than one group."""
+    dtype, m, hq, hkv, d = "bf16", 2900, 32, 8, 128
+    cfg = lcfg(dtype, hq, hkv, d, hid)
+    g = np.random.default_rng(91)
+    n_rows = 3100
+    hidden = rnd(92, (n_rows, hid), dtype)
+    w = [rnd(93 + i, (h * d, hid), dtype, 1.0 / np.sqrt(hid)) for i, h in enumerate((hq, hkv, hkv))]
+    rows = np.sort(g.choice(n_rows, m, replace=False)).astype(np.int32)
+    pos = np.sort(g.choice(200000, m, replace=False)).astype(np.int32)
+    want = O.project_qkv_rows(hidden.astype(np.float64), rows, pos,
+                              *[x.astype(np.float64) for x in w], hq, hkv, d, cfg.rope_theta,
+                              dtype)
+    args = (dev(hidden, dtype, gpu_device), torch.from_numpy(rows).to(gpu_device),
+            torch.from_numpy(pos).to(gpu_device), *[dev(x, dtype, gpu_device) for x in w])
+    ws = torch.empty(max(api.pkv_workspace_bytes(api.CALL_GATHER_QKV_PROJ, cfg, 0, m), 256),
+                     dtype=torch.uint8, device=gpu_device)
+    outs = [torch.full((m, h, d), float("nan"), dtype=cfg.torch_dtype, device=gpu_device)
+            for h in (hq, hkv, hkv)]
+    api.pkv_gather_qkv_proj(cfg, *args, *outs, ws=ws)
+    for o, wnt in zip(outs, want):
+        assert torch.isfinite(o.float()).all()
+        assert rel_err(host(o), wnt) <= TOL[dtype]
+
+
 # ------------------------------------------------------------------ attention
 
 @pytest.mark.parametrize("dtype,m,n_keys,hq,hkv,d", [
