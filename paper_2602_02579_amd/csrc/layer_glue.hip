@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(const T* __restrict__
         for (int i = 0; i < 8; ++i) {
             const int c = i * 64 + lane;
             if (c < n_chunks) {
-                v[i] = hp[c];
+                v[i] = __builtin_nontemporal_load(hp + c);   // every row is read once
 #pragma unroll
                 for (int e = 0; e < N; ++e) {
                     const float f = Elem<T>::to_f32(v[i][e]);
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void rmsnorm_rows_kernel(const T* __restrict__
 #pragma unroll
                 for (int e = 0; e < N; ++e)
                     o[e] = Elem<T>::from_f32(Elem<T>::to_f32(v[i][e]) * r * Elem<T>::to_f32(w[e]));
-                yp[c] = o;
+                __builtin_nontemporal_store(o, yp + c);
             }
         }
     } else {

@@ -48,8 +48,12 @@ __global__ __launch_bounds__(256) void rope_restore_kernel(
 #pragma unroll
             for (int u = 0; u < HB; ++u) {
                 if (h0 + u < n_heads) {
-                    a[u] = *reinterpret_cast<const vec_t*>(src + (h0 + u) * head_dim);
-                    b[u] = *reinterpret_cast<const vec_t*>(src + (h0 + u) * head_dim + half);
+                    // streamed once: non-temporal, so that the lines do not displace what the
+                    // caches hold for the kernels around this one
+                    a[u] = __builtin_nontemporal_load(
+                        reinterpret_cast<const vec_t*>(src + (h0 + u) * head_dim));
+                    b[u] = __builtin_nontemporal_load(
+                        reinterpret_cast<const vec_t*>(src + (h0 + u) * head_dim + half));
                 }
             }
         };
@@ -70,8 +74,9 @@ __global__ __launch_bounds__(256) void rope_restore_kernel(
                         ra[j] = Elem<T>::from_f32(x * cs[j] - y * sn[j]);
                         rb[j] = Elem<T>::from_f32(y * cs[j] + x * sn[j]);
                     }
-                    *reinterpret_cast<vec_t*>(dst + (h0 + u) * head_dim) = ra;
-                    *reinterpret_cast<vec_t*>(dst + (h0 + u) * head_dim + half) = rb;
+                    __builtin_nontemporal_store(ra, reinterpret_cast<vec_t*>(dst + (h0 + u) * head_dim));
+                    __builtin_nontemporal_store(
+                        rb, reinterpret_cast<vec_t*>(dst + (h0 + u) * head_dim + half));
                 }
             }
         }
