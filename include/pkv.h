@@ -59,6 +59,15 @@
  *   head_dim * (n_keys rounded up to 64) * 2 < 2^32 and rows * n_q_heads
  *   (query tokens * n_q_heads) < 2^31; beyond that they return
  *   PKV_ERR_UNSUPPORTED.
+ * Environment: three variables change HOW pkv_sparse_row_attn (bf16, head_dim
+ *   128) works, never what it computes; they exist for measurements and
+ *   tests.  PKV_ATTN_WAVES=4 (read once per process): workgroups of four
+ *   waves instead of eight.  PKV_ATTN_VT=1 / 0 (read at every call): always
+ *   / never make a transposed copy of the value cache in the workspace
+ *   before the main kernel (unset: decided by problem size).
+ *   PKV_ATTN_RANGES=n (read once): process the keys of every row tile in n
+ *   ranges (unset: decided by problem size).  Workspace sizes do not depend
+ *   on the first two; set the third before asking for sizes.
  */
 #ifndef PKV_H
 #define PKV_H
