@@ -3,9 +3,10 @@
 // (Paper: Algorithm 1 first stage, alpha_l = Softmax(Q_s K'^T / sqrt(d_k)) over the
 // context keys; Sec. 4.2 mean over the user-query tokens; Appendix E mean over heads.)
 //
-// A workgroup of NW = 8 waves (two per SIMD, so that the softmax arithmetic of one wave
-// runs under the matrix instructions and waits of the other) owns 256 columns (query token,
-// head of one kv group) and one split of the key range; a wave owns 256 / NW of them.  The columns are the ROWS of the MFMA tile here,
+// A workgroup of 8 waves (two per SIMD, so that the softmax arithmetic of one wave runs
+// under the matrix instructions and waits of the other) owns 256 columns (query token,
+// head of one kv group) and one split of the key range; a wave owns 32 of them.  The
+// columns are the ROWS of the MFMA tile here,
 //     S [32 cols x 32 keys] = Q (A operand, registers) x K^T (B operand, LDS)
 // so that a lane holds one key (l % 32) of a 32-key block and, in its 16
 // accumulator registers, 16 of the 32 columns.  Sums over keys (pass 1: the
@@ -17,14 +18,15 @@
 //           split.  The reference of a lane's column is fixed by the first tile and
 //           is raised only when a tile's probabilities leave the safe range, which is
 //           detected from their sum (no maximum in the hot loop).
-//   pass 2  per key: sum over the workgroup's columns of exp2(s c - lse2[col]),
-//           one partial per (workgroup column block, wave); finish_score_kernel adds
-//           the partials of a key in a fixed order, so the score is deterministic.
+//   pass 2  per key: sum over the workgroup's columns of exp2(s c - lse2[col]);
+//           waves w and w + 4 add their sums through LDS and one partial per (workgroup
+//           column block, wave pair) goes to memory; finish_score_kernel adds the
+//           partials of a key in a fixed order, so the score is deterministic.
 //
 // K tiles of 64 keys go through a 6-stage LDS ring (16 KB per stage), requested five
 // tiles ahead; layout and 16-byte-chunk XOR swizzle are those of the attention
-// kernel.  One softmax step (two scores) follows every MFMA; the operands of the
-// next tile are re-read from LDS in the same rhythm.
+// kernel.  One softmax step (two scores) follows every MFMA; each MFMA's key operand
+// is read from LDS six MFMAs before it, into a ring of eight registers quadruples.
 #include <atomic>
 
 #include "score_common.h"

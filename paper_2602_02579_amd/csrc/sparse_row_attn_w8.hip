@@ -20,6 +20,11 @@
 //     P(u+1)   from S^T(u+1), one score after each MFMA,
 //     O^T     += V^T(u) P^T(u).
 // Every result is consumed a full sub-step after it was produced.
+//
+// Two instantiations: <false> reads V^T tiles from a transposed copy of the value cache
+// that a pre-pass makes; <true> fills LDS with the value rows as the cache holds them and
+// transposes them on the way out (ds_read_b64_tr_b16: 1.5 instead of 1 LDS instruction per
+// MFMA, a loop ~2.5 % slower, no pre-pass).  The launcher picks by problem size.
 #include <algorithm>
 #include <atomic>
 
