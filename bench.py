@@ -706,26 +706,37 @@ def main():
     torch.cuda.synchronize()
     result["ms_per_step_fused_cache_update"] = round(
         (time.perf_counter() - t0) / args.steps * 1e3, 4)
+    def section(key, fn):
+        """The sections below are outside `value`: one that fails (memory, an unsupported
+        shape) says so in its place and the line is still printed."""
+        try:
+            result[key] = fn()
+        except Exception as exc:   # noqa: BLE001
+            result[key] = {"error": f"{type(exc).__name__}: {exc}"}
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+
     if not args.no_extras:
         # the same two passes replayed from a captured graph: what is left of the launch
         # gaps between the small kernels at the head of a pass (outside `value`, whose timed
         # region carries the events of the roofline and is launched call by call)
-        result["ms_per_step_graph_replay"] = graph_replay_ms(sr, layers, args.steps)
-        result["ms_per_step_fused_cache_update_graph_replay"] = graph_replay_ms(
-            sr_f, layers, args.steps)
+        section("ms_per_step_graph_replay", lambda: graph_replay_ms(sr, layers, args.steps))
+        section("ms_per_step_fused_cache_update_graph_replay",
+                lambda: graph_replay_ms(sr_f, layers, args.steps))
     del sr_f
     if not args.no_extras and cfg.dtype == "bf16":
-        result["diagnostics"] = diagnostics_report(device, layers[0], plants, sr)
+        section("diagnostics", lambda: diagnostics_report(device, layers[0], plants, sr))
     del layers, sr
     torch.cuda.empty_cache()
     if not args.no_extras and cfg.dtype == "bf16":
-        result["bandwidth"] = bandwidth(cfg, device)
-        result["extras"] = extras(device)
+        section("bandwidth", lambda: bandwidth(cfg, device))
+        section("extras", lambda: extras(device))
     if args.model_layers > 0 and cfg.dtype == "bf16":
-        result["carried_model"] = carried_model(cfg.with_(n_layers=1), device,
-                                                args.model_layers)
+        section("carried_model",
+                lambda: carried_model(cfg.with_(n_layers=1), device, args.model_layers))
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg.with_(n_layers=1, n_score_layers=1))
+        section("cpu_baseline",
+                lambda: cpu_baseline(cfg.with_(n_layers=1, n_score_layers=1)))
     print(json.dumps(result))
 
 
