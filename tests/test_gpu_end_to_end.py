@@ -6,7 +6,9 @@ bit-identical to the restored/assembled cache; K/V and attention outputs are
 within max|a-b|/max|b| <= 1e-4 (fp32) / 2e-2 (bf16); log-sum-exp within 1e-3 /
 4e-3 absolute.  At the 32k benchmark configuration every recomputed row is compared;
 the two-scoring-layer stack at ratios 0.1 and 0.4 compares the caches of every layer
-on every row and the attention on the edge rows of every row tile."""
+on every row and the attention on the edge rows of every row tile; the whole 32-layer
+stack is checked by the invariants of Algorithm 1 in every layer and by the oracle on
+sampled rows of three layers."""
 
 import numpy as np
 import pytest
@@ -301,3 +303,117 @@ def test_config4_full_size_three_of_the_32_layers_two_fused_scoring_layers(gpu_d
     assert rel_err(host(sr.q)[pick], q[pick]) <= TOL[cfg.dtype]
     assert rel_err(host(sr.out)[pick], out) <= TOL[cfg.dtype]
     check_lse(cfg, sr, dev_layers[-1], host(sr.lse)[pick], lse, rows[pick], pick)
+
+
+def device_layers(cfg, device, n_layers, seed):
+    """Layers of cfg's shape drawn on the device (nothing planted; no margin repair is
+    needed where no oracle selection is compared)."""
+    dt = pipeline.layer_cfg(cfg).torch_dtype
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    n, qn = cfg.n_ctx, cfg.n_query
+    hq, hkv, d, hid = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.hidden
+
+    def normal(*shape, scale=1.0):
+        return (torch.randn(shape, generator=gen, device=device) * scale).to(dt)
+
+    layers = []
+    for _ in range(n_layers):
+        hidden = torch.randn((n + qn, hid), generator=gen, device=device)
+        hidden[:n] += 0.5 * torch.randn(hid, generator=gen, device=device)
+        hidden[n:] = torch.randn(hid, generator=gen, device=device) + 0.3 * hidden[n:]
+        L = dict(k_nope=normal(n, hkv, d), hidden=hidden.to(dt),
+                 wq=normal(hq * d, hid, scale=0.02), wk=normal(hkv * d, hid, scale=0.02),
+                 wv=normal(hkv * d, hid, scale=0.02),
+                 v_cache=torch.zeros((n + qn, hkv, d), dtype=dt, device=device),
+                 k_cache=torch.zeros((n + qn, hkv, d), dtype=dt, device=device))
+        L["v_cache"][:n] = normal(n, hkv, d)
+        del hidden
+        layers.append(L)
+    return layers
+
+
+def test_config4_all_32_layers_at_full_size(gpu_device):
+    """The whole 32-layer stack of cfg 4 (N = 32768, 128 query tokens, r = 0.2, scoring fused
+    over the first two layers) in one pass, checked by what must hold at any size
+    (Algorithm 1): one selection for every layer; in every layer the rows outside it are
+    the restored keys / the assembled values bit for bit and the rows inside it are what
+    the projection of that layer's hidden rows gives; the fused score sums to the number of
+    scoring layers.  On three of the layers, sampled recomputed rows and sampled attention
+    rows are also compared with the oracle."""
+    from paper_2602_02579_amd import api
+    cfg = synth.CONFIGS[4]
+    assert cfg.n_layers == 32 and cfg.n_score_layers == 2
+    dev = gpu_device
+    layers = device_layers(cfg, dev, cfg.n_layers, seed=404)
+    v0 = [L["v_cache"][:cfg.n_ctx].clone() for L in layers]
+    sr = pipeline.SelectiveRecompute(cfg, dev)
+    lc = sr.lc
+    n, qn, k, m = cfg.n_ctx, cfg.n_query, sr.k, sr.m
+    spot = (3, 17, 31)
+    kept = {}
+
+    # the pass, layer by layer as SelectiveRecompute.run does it, keeping what the last call
+    # of a layer leaves in the shared buffers for the three spot-checked layers
+    for L in layers:
+        sr.restore(L)
+    for li in range(cfg.n_score_layers):
+        sr.score_layer(layers[li], accumulate=li > 0)
+    sr.select()
+    rows_after_select = sr.rows.clone()
+    for li, L in enumerate(layers):
+        sr.recompute_layer(L)
+        if li in spot:
+            kept[li] = (sr.q.clone(), sr.out.clone(), sr.lse.clone())
+    torch.cuda.synchronize()
+
+    assert torch.equal(sr.rows, rows_after_select)            # one selection, never touched again
+    rows = sr.rows.cpu().numpy()
+    assert np.array_equal(rows[k:], np.arange(n, n + qn))
+    assert np.all(np.diff(rows[:k]) > 0) and rows[0] >= 0 and rows[k - 1] < n
+    assert abs(float(sr.score.sum()) - cfg.n_score_layers) < 2e-3
+    # the selection is the top k of the fused score (ties: lower index)
+    sc = sr.score.cpu().numpy()
+    assert np.array_equal(rows[:k], O.topk_select(sc.astype(np.float64), k))
+
+    keep = torch.ones(n, dtype=torch.bool, device=dev)
+    keep[sr.rows[:k].long()] = False
+    ws = torch.empty_like(sr.ws)
+    for li, L in enumerate(layers):
+        # reused rows: restored keys, assembled values
+        restored = torch.empty_like(L["k_cache"][:n])
+        api.pkv_rope_restore(lc, L["k_nope"], restored, None, 0)
+        assert torch.equal(L["k_cache"][:n][keep], restored[keep]), li
+        assert torch.equal(L["v_cache"][:n][keep], v0[li][keep]), li
+        # recomputed rows: this layer's projection (the same kernel, called on its own)
+        q = torch.empty_like(sr.q)
+        kn, vn = torch.empty_like(sr.k_new), torch.empty_like(sr.v_new)
+        api.pkv_gather_qkv_proj(lc, L["hidden"], sr.rows, sr.rows, L["wq"], L["wk"], L["wv"],
+                                q, kn, vn, ws=ws)
+        assert torch.equal(L["k_cache"][sr.rows.long()], kn), li
+        assert torch.equal(L["v_cache"][sr.rows.long()], vn), li
+        assert not torch.equal(L["k_cache"][:n][~keep], restored[~keep]), li
+        del restored, q, kn, vn
+    assert torch.isfinite(sr.out.float()).all() and torch.isfinite(sr.lse).all()
+
+    # oracle on samples of three layers
+    g = np.random.default_rng(405)
+    geo = dict(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+               theta=cfg.theta)
+    for li in spot:
+        L = layers[li]
+        pick = np.unique(np.concatenate([[0, k - 1, k, m - 1], g.choice(m, 28, replace=False)]))
+        hid = host(L["hidden"][torch.from_numpy(rows[pick]).long().to(dev)])
+        q_w, k_w, v_w = O.project_qkv_rows(hid, np.arange(len(pick)), rows[pick], host(L["wq"]),
+                                           host(L["wk"]), host(L["wv"]), dtype=cfg.dtype, **geo)
+        q_g, out_g, lse_g = kept[li]
+        sel = torch.from_numpy(rows[pick]).long().to(dev)
+        assert rel_err(host(q_g)[pick], q_w) <= TOL[cfg.dtype]
+        assert rel_err(host(L["k_cache"][sel]), k_w) <= TOL[cfg.dtype]
+        assert rel_err(host(L["v_cache"][sel]), v_w) <= TOL[cfg.dtype]
+        # attention of a few rows over the caches this layer ended with
+        few = pick[[0, len(pick) // 3, 2 * len(pick) // 3, len(pick) - 1]]
+        out_w, lse_w = oracle_attention(host(q_g)[few], host(L["k_cache"]), host(L["v_cache"]),
+                                        rows[few], cfg.dtype)
+        assert rel_err(host(out_g)[few], out_w) <= TOL[cfg.dtype]
+        assert np.abs(host(lse_g)[few] - lse_w).max() <= 4e-3
