@@ -13,8 +13,8 @@ struct AttnParams {
     const bf16_t* k;
     const bf16_t* vt;        // [hkv, D, n_pad], zero beyond n_keys
     const bf16_t* v;         // [n_keys, hkv, D] as the cache holds it, or nullptr: when set, the
-                             // eight-wave pipelined kernel reads it and vt is filled only if a
-                             // tile gets marked for the exact kernel
+                             // eight-wave pipelined kernel and the exact kernel that redoes its
+                             // marked tiles read it, and vt is not used
     const int32_t* row_pos;  // [m] or nullptr when fixed_limit >= 0
     bf16_t* out;             // [m, hq, D]
     float* lse;              // [m, hq] or nullptr

@@ -240,9 +240,17 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
             stage_k[i] = *reinterpret_cast<const uint4*>(
                 p.k + ((int64_t)kk * p.hkv + g) * D + dch * 8);
             if (kPV) {
-                const int d = c / (kBN / 8), kch = c % (kBN / 8);
-                stage_v[i] = *reinterpret_cast<const uint4*>(
-                    p.vt + ((int64_t)g * D + d) * p.n_pad + t0 + kch * 8);
+                if (p.v) {
+                    // no V^T copy was made (the pipelined kernel read the cache as it is):
+                    // the same piece of the value row, transposed on its way into LDS.  Rows
+                    // past the cache repeat its last row; their probabilities are zero.
+                    stage_v[i] = *reinterpret_cast<const uint4*>(
+                        p.v + ((int64_t)kk * p.hkv + g) * D + dch * 8);
+                } else {
+                    const int d = c / (kBN / 8), kch = c % (kBN / 8);
+                    stage_v[i] = *reinterpret_cast<const uint4*>(
+                        p.vt + ((int64_t)g * D + d) * p.n_pad + t0 + kch * 8);
+                }
             }
         }
     };
@@ -254,9 +262,16 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnParams p) {
             *reinterpret_cast<uint4*>(k_lds + buf * L::kElems + key * L::kStride + dch * 8) =
                 stage_k[i];
             if (kPV) {
-                const int d = c / (kBN / 8), kch = c % (kBN / 8);
-                *reinterpret_cast<uint4*>(v_lds + buf * L::vElems + d * L::vStride + kch * 8) =
-                    stage_v[i];
+                if (p.v) {
+                    const bf16x8 e = __builtin_bit_cast(bf16x8, stage_v[i]);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        v_lds[buf * L::vElems + (dch * 8 + j) * L::vStride + key] = e[j];
+                } else {
+                    const int d = c / (kBN / 8), kch = c % (kBN / 8);
+                    *reinterpret_cast<uint4*>(v_lds + buf * L::vElems + d * L::vStride + kch * 8) =
+                        stage_v[i];
+                }
             }
         }
     };
@@ -453,22 +468,6 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(
     if (zero && blockIdx.x == 0 && blockIdx.y == 0)
         for (int i = threadIdx.x; i < n_zero; i += 256) zero[i] = 0;
     transpose_v_tile(v, vt, n_keys, n_pad, hkv, d, blockIdx.x, blockIdx.y, tile);
-}
-
-// The pipelined kernel that reads the values as the cache holds them needs no V^T; the
-// exact kernel that redoes the tiles it marked does.  This launch between the two makes the
-// copy only when something was marked (*marked != 0): normally every workgroup leaves at
-// once.  A fixed grid walks the tiles.
-__global__ __launch_bounds__(256) void transpose_v_if_marked_kernel(
-    const bf16_t* __restrict__ v, bf16_t* __restrict__ vt, int n_keys, int n_pad,
-    int hkv, int d, const int* marked) {
-    __shared__ bf16_t tile[64][64 + 2];
-    if (*marked == 0) return;   // the same for every thread of the launch
-    const int nx = n_pad / 64, ny = hkv * d / 64;
-    for (int t = blockIdx.x; t < nx * ny; t += gridDim.x) {
-        transpose_v_tile(v, vt, n_keys, n_pad, hkv, d, t % nx, t / nx, tile);
-        __syncthreads();   // the tile buffer is reused
-    }
 }
 
 // What the pipelined kernel expects at zero when no V^T pre-pass runs before it.
@@ -741,7 +740,8 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         // The eight-wave pipelined kernel can transpose the values on their way out of LDS
         // instead of reading a V^T copy made here.  Its loop is then ~2.5 % slower (half as
         // many bytes per LDS instruction), the copy costs its bytes at ~5.5 TB/s plus a launch,
-        // and doing without it costs two small launches: the copy is skipped when that is the
+        // and doing without it costs one small launch (a fill kernel for the counters that
+        // the pre-pass otherwise clears): the copy is skipped when that is the
         // cheaper side, which it is for the user-query rows and for short launches over long
         // caches (measured: 128 rows over 32k keys 110 -> 94 us, 1766 rows 477 -> 468 us,
         // 6681 rows 1490 -> 1501 us, 883 rows over 4k keys 77 -> 81 us).
@@ -753,7 +753,7 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
                 const double copy_us = 3.0 + (double)n_pad * cfg.n_kv_heads * d * 4.0 / 5.5e6;
                 const double main_us = 1.68 * (double)ceil_div(m, bm) * cfg.n_kv_heads *
                                        (double)(n_pad / 64) * (m > 768 ? 0.5 : 1.0) / 256.0;
-                nat_v = copy_us - 6.0 > 0.025 * main_us;
+                nat_v = copy_us - 4.0 > 0.025 * main_us;
             } else {
                 nat_v = src == 0;
             }
@@ -804,13 +804,7 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         }
         const pkv_status rc = launch_attn_dma128(p, st);
         if (rc != PKV_OK) return rc;
-        if (nat_v) {
-            const int n_vt_tiles = (n_pad / 64) * (cfg.n_kv_heads * d / 64);
-            hipLaunchKernelGGL(transpose_v_if_marked_kernel, dim3((unsigned)std::min(n_vt_tiles, 2048)),
-                               dim3(256), 0, st, (const bf16_t*)v_cache, vt, (int)n_keys, n_pad,
-                               cfg.n_kv_heads, d, p.flags + p.n_tiles * p.hkv);
-            if (launch_status() != PKV_OK) return PKV_ERR_LAUNCH;
-        }
+        // (p.v set: the exact kernel, too, reads the cache as it is for the tiles it redoes)
         return launch_attn_mfma<128, true>(p, st);
     }
     const int block = d <= 64 ? 64 : (d <= 128 ? 128 : 256);

@@ -558,7 +558,7 @@ pkv_status launch_attn_w8_main(const AttnParams& p, int n_cu, hipStream_t st) {
     }
     // one workgroup per CU (its LDS admits no second one), or per job if there are fewer
     const int64_t grid = std::min<int64_t>((int64_t)p.n_tiles * p.dma_splits * p.hkv, n_cu);
-    if (p.v)   // the values as the cache holds them; p.vt is then only the repair pass's
+    if (p.v)   // the values as the cache holds them; p.vt is then not used
         hipLaunchKernelGGL(attn_w8_kernel<true>, dim3((unsigned)grid), dim3(kThreads), kLdsBytes,
                            st, p);
     else
