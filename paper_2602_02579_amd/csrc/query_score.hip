@@ -363,6 +363,7 @@ pkv_status launch_query_score(const pkv_layer_cfg& cfg, const void* q,
         sp_.k = (const bf16_t*)k;
         sp_.part_ml = part_ml;
         sp_.lse2 = lse2;
+        sp_.lse_factor = 1.0f;   // merge_lse_kernel writes log2-domain values
         sp_.part_score = part_score;
         sp_.nq = (int)nq; sp_.n_ctx = (int)n_ctx; sp_.hq = hq; sp_.hkv = hkv; sp_.group = hq / hkv;
         sp_.n_cblk = sp.n_cblk; sp_.n_splits = sp.n_splits; sp_.split_len = sp.split_len;
@@ -451,8 +452,6 @@ pkv_status launch_query_score_lse(const pkv_layer_cfg& cfg, const void* q, const
     // behind the (unused here) partial normalisers
     unsigned char* base = (unsigned char*)ws;
     float* lse2 = (float*)base;
-    hipLaunchKernelGGL(lse_to_log2_kernel, dim3((unsigned)ceil_div(ncol, 256)), dim3(256), 0,
-                       st, lse, lse2, ncol);
     if (!row_pos && score_dma128_supported(cfg, n_ctx, nq)) {
         const ScorePlan sp = plan_score_dma128(cfg, n_ctx, nq);
         float* part_score = (float*)(base + align_up((size_t)ncol * sizeof(float)) +
@@ -460,7 +459,8 @@ pkv_status launch_query_score_lse(const pkv_layer_cfg& cfg, const void* q, const
         ScoreParams sp_ = {};
         sp_.q = (const bf16_t*)q;
         sp_.k = (const bf16_t*)k;
-        sp_.lse2 = lse2;
+        sp_.lse2 = lse;   // natural log: the kernel converts as it loads
+        sp_.lse_factor = 1.4426950408889634f;
         sp_.part_score = part_score;
         sp_.nq = (int)nq; sp_.n_ctx = (int)n_ctx; sp_.hq = hq; sp_.hkv = hkv; sp_.group = hq / hkv;
         sp_.n_cblk = sp.n_cblk; sp_.n_splits = sp.n_splits; sp_.split_len = sp.split_len;
@@ -472,6 +472,8 @@ pkv_status launch_query_score_lse(const pkv_layer_cfg& cfg, const void* q, const
                            1.0f / (float)ncol, accumulate);
         return launch_status();
     }
+    hipLaunchKernelGGL(lse_to_log2_kernel, dim3((unsigned)ceil_div(ncol, 256)), dim3(256), 0,
+                       st, lse, lse2, ncol);
     const SplitPlan sp = plan_splits(cfg, n_ctx, nq);
     float* part_score = (float*)(base + align_up((size_t)ncol * sizeof(float)) +
                                  align_up((size_t)sp.n_splits * ncol * 2 * sizeof(float)));

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
                 const bool valid = col < ncol_g;
                 const int qi = valid ? col / p.group : 0;
                 const int h = g * p.group + (valid ? col % p.group : 0);
-                norm[cb][r] = valid ? p.lse2[(int64_t)qi * p.hq + h] : INFINITY;
+                norm[cb][r] = valid ? p.lse2[(int64_t)qi * p.hq + h] * p.lse_factor : INFINITY;
             } else {
                 msc[cb][r] = 0.f;
                 lsum[cb][r] = 0.f;

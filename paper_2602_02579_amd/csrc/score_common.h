@@ -9,7 +9,8 @@ struct ScoreParams {
     const bf16_t* q;        // [nq, hq, D]
     const bf16_t* k;        // [n_ctx, hkv, D]
     float* part_ml;         // pass 1 out: [n_splits, nq * hq, 2] (max in raw logits, sum)
-    const float* lse2;      // pass 2 in:  [nq * hq] log2-domain normaliser
+    const float* lse2;      // pass 2 in:  [nq * hq] normaliser, times lse_factor = its log2-domain
+    float lse_factor;       //             value (1, or log2(e) for a natural-log normaliser)
     float* part_score;      // pass 2 out: [n_parts, n_ctx]
     int nq, n_ctx, hq, hkv, group;
     int n_cblk;             // blocks of 256 columns per kv group
