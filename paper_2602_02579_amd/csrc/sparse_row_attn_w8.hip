@@ -283,6 +283,11 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) vaddr[q] = v0 ^ (q << 5);
         }
+        // the value stages lie behind the 64 KB of key stages: with that base inside the lane's
+        // address every stage and block offset of a value read fits the 16-bit immediate of
+        // the LDS instruction, and no address arithmetic is left in the loop
+#pragma unroll
+        for (int q = 0; q < 4; ++q) vaddr[q] += NS * kStageK;
     }
     const float c2 = p.scale_log2;
 
@@ -307,13 +312,13 @@ __global__ __launch_bounds__(kThreads) void attn_w8_kernel(AttnParams p) {
         smem + (ST) * kStageK + (H) * 32 * 256 + kaddr[KCI]);
 #define W8_LOAD_VA1(ST, H, KK, DBI)                                                      \
     if (kNatV) {                                                                         \
-        const unsigned char* a_ = smem + NS * kStageK + (ST) * kStageV +                 \
+        const unsigned char* a_ = smem + (ST) * kStageV +                                \
                                   (32 * (H) + 16 * (KK)) * 256 + vaddr[DBI];             \
         const bf16x4 lo_ = lds_read_tr(a_), hi_ = lds_read_tr(a_ + 4 * 256);             \
         va[KK][DBI] = __builtin_shufflevector(lo_, hi_, 0, 1, 2, 3, 4, 5, 6, 7);         \
     } else {                                                                             \
         va[KK][DBI] = *reinterpret_cast<const bf16x8*>(                                  \
-            smem + NS * kStageK + (ST) * kStageV + (DBI) * 32 * 128 + vaddr[2 * (H) + (KK)]); \
+            smem + (ST) * kStageV + (DBI) * 32 * 128 + vaddr[2 * (H) + (KK)]);           \
     }
 
     // exponent of element R of score buffer S whose first key is T0
