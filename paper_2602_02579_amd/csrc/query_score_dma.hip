@@ -64,6 +64,7 @@ constexpr int kScoreWaves = 8;
 template <int PASS, int NW>
 __global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
     static_assert(NW == 8, "256 columns over 8 waves of 32 (the operand ring below assumes it)");
+    static_assert(NS == 6, "the main loop is unrolled once round the ring");
     constexpr int NCB = 8 / NW;      // 32-column blocks of a wave
     constexpr int FILLS = 16 / NW;   // fill instructions of a wave per tile (4 key rows each)
     extern __shared__ __align__(16) unsigned char smem[];
@@ -149,9 +150,19 @@ __global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
     // LDS kLook MFMAs before their use.
     constexpr int kLook = 6;
     bf16x8 kq[8];
-    auto load_op = [&](int T, int i, int slot) {
-        kq[slot] = *reinterpret_cast<const bf16x8*>(smem + (T % NS) * kStage + (i & 1) * 32 * 256 +
-                                                    kaddr[i >> 1]);
+    // STAGE = the ring stage of tile T when the caller knows it at compile time (the main loop
+    // is unrolled over the ring), else -1.  With a known stage the whole offset fits the
+    // 16-bit immediate of the LDS instruction - from a second copy of the lane addresses,
+    // 64 KB on, for stages 4 and 5 - and no address arithmetic is left in the loop.
+    uint32_t kaddr_hi[KC];
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) kaddr_hi[kc] = kaddr[kc] + 4 * kStage;
+    auto load_op = [&](int T, int STAGE, int i, int slot) {
+        const unsigned char* a;
+        if (STAGE < 0) a = smem + (T % NS) * kStage + kaddr[i >> 1];
+        else if (STAGE < 4) a = smem + STAGE * kStage + kaddr[i >> 1];
+        else a = smem + (STAGE - 4) * kStage + kaddr_hi[i >> 1];
+        kq[slot] = *reinterpret_cast<const bf16x8*>(a + (i & 1) * 32 * 256);
     };
 
     // ---- per-pass state --------------------------------------------------------------------
@@ -193,8 +204,8 @@ __global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {   // S(0), operands through the ring two at a time
             if ((i & 1) == 0) {
-                load_op(0, i, i & 7);
-                load_op(0, i + 1, (i + 1) & 7);
+                load_op(0, 0, i, i & 7);
+                load_op(0, 0, i + 1, (i + 1) & 7);
             }
             s_a[0][i & 1] = mfma32(qreg[0][i >> 1], kq[i & 7], i < 2 ? z : s_a[0][i & 1]);
         }
@@ -202,7 +213,7 @@ __global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
     wait_vm<FILLS * (NS - 3)>();   // tile 1
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < kLook; ++i) load_op(1, i, i);
+    for (int i = 0; i < kLook; ++i) load_op(1, 1, i, i);
     wait_vm<FILLS * (NS - 4)>();   // tile 2 (the look-ahead of tile 0's last MFMAs reads it)
     __syncthreads();
 
@@ -237,8 +248,8 @@ __global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
 
     // One tile: CUR = S(T) is turned into sums while NXT = S(T+1) is formed; the operand of
     // MFMA i + kLook (of tile T+1, or of tile T+2 behind the tile's end) is requested after
-    // MFMA i.
-#define PKV_SCORE_TILE(CUR, NXT, T, RAGGED)                                                      \
+    // MFMA i.  ST1, ST2 = the ring stages of tiles T+1 and T+2 if known at compile time, else -1.
+#define PKV_SCORE_TILE(CUR, NXT, T, ST1, ST2, RAGGED)                                            \
     {                                                                                    \
         const int t0_ = key_begin + (T) * kTile;                                         \
         dma_tile((T) + NS - 1);                                                          \
@@ -251,8 +262,8 @@ __global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
                                    0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};              \
                 const int i_ = kc * 2 + q4;                                              \
                 NXT[0][q4] = mfma32(qreg[0][kc], kq[i_ & 7], kc == 0 ? z_ : NXT[0][q4]); \
-                if (i_ + kLook < 16) load_op((T) + 1, i_ + kLook, (i_ + kLook) & 7);     \
-                else load_op((T) + 2, i_ + kLook - 16, (i_ + kLook) & 7);                \
+                if (i_ + kLook < 16) load_op((T) + 1, ST1, i_ + kLook, (i_ + kLook) & 7); \
+                else load_op((T) + 2, ST2, i_ + kLook - 16, (i_ + kLook) & 7);           \
                 /* softmax step: column (scb_, sr_), keys of both key blocks.  The    */ \
                 /* exponents were formed one step earlier and the results are added   */ \
                 /* one step later, so nothing waits on the transcendental unit.       */ \
@@ -353,17 +364,26 @@ __global__ __launch_bounds__(64 * NW) void score_dma128_kernel(ScoreParams p) {
     // only the last tile of a split can reach past key_end
     const bool last_ragged = key_begin + n_iter * kTile > key_end;
     int T = 0;
+    // once round the ring per trip: T is a multiple of NS = 6 here, so every stage is a constant
+    for (; T + 6 < n_iter; T += 6) {
+        PKV_SCORE_TILE(s_a, s_b, T, 1, 2, false)
+        PKV_SCORE_TILE(s_b, s_a, T + 1, 2, 3, false)
+        PKV_SCORE_TILE(s_a, s_b, T + 2, 3, 4, false)
+        PKV_SCORE_TILE(s_b, s_a, T + 3, 4, 5, false)
+        PKV_SCORE_TILE(s_a, s_b, T + 4, 5, 0, false)
+        PKV_SCORE_TILE(s_b, s_a, T + 5, 0, 1, false)
+    }
     for (; T + 2 < n_iter; T += 2) {
-        PKV_SCORE_TILE(s_a, s_b, T, false)
-        PKV_SCORE_TILE(s_b, s_a, T + 1, false)
+        PKV_SCORE_TILE(s_a, s_b, T, -1, -1, false)
+        PKV_SCORE_TILE(s_b, s_a, T + 1, -1, -1, false)
     }
     if (T + 2 == n_iter) {
-        PKV_SCORE_TILE(s_a, s_b, T, false)
-        if (last_ragged) PKV_SCORE_TILE(s_b, s_a, T + 1, true)
-        else PKV_SCORE_TILE(s_b, s_a, T + 1, false)
+        PKV_SCORE_TILE(s_a, s_b, T, -1, -1, false)
+        if (last_ragged) PKV_SCORE_TILE(s_b, s_a, T + 1, -1, -1, true)
+        else PKV_SCORE_TILE(s_b, s_a, T + 1, -1, -1, false)
     } else {
-        if (last_ragged) PKV_SCORE_TILE(s_a, s_b, T, true)
-        else PKV_SCORE_TILE(s_a, s_b, T, false)
+        if (last_ragged) PKV_SCORE_TILE(s_a, s_b, T, -1, -1, true)
+        else PKV_SCORE_TILE(s_a, s_b, T, -1, -1, false)
     }
     wait_vm<0>();   // nothing may still be writing LDS when the workgroup retires
     if (PASS == 2 && NW == 8 && wave < 4 && pend_t0 >= 0) {
