@@ -40,10 +40,10 @@ if ROOT not in sys.path:
 from paper_2602_02579_amd import api, model, pipeline, synth  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
-# HBM bytes per pkv_sparse_row_attn launch (V^T pre-pass + main kernel), from the
+# HBM bytes per pkv_sparse_row_attn launch (its main kernel; the others move nothing), from the
 # FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/hot_path_cfg3_hbm_traffic.txt
 # (counters cannot be read from inside this process; the figure is for that workload only)
-MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 2.051e9}
+MEASURED_ATTN_TRAFFIC_BYTES = {"cfg3-llama8b-32k": 1.744e9}
 TRAFFIC_SOURCE = ("profiles/hot_path_cfg3_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / "
                   "WRITE_SIZE runs of this program, commands in the file; not read live)")
 PEAK_F32_TFLOPS = 157.3
@@ -692,8 +692,10 @@ def main():
                      "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(cfg.name),
                      "traffic_source": TRAFFIC_SOURCE,
                      "flops_per_launch": flops, "avg_launch_s": t_attn,
-                     "launch": "pkv_sparse_row_attn = V^T pre-pass + attn_w8_kernel + "
-                               "repair pass, timed with events on the launch stream"},
+                     "launch": "pkv_sparse_row_attn = a small first kernel (clears the work "
+                               "counters; at the largest sizes it also makes a V^T copy) + "
+                               "attn_w8_kernel + repair pass, timed with events on the launch "
+                               "stream"},
         "breakdown": breakdown,
     }
     # the same pass with steps 4a + 4b fused into one call (outside `value`)

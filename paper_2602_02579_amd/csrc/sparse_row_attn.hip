@@ -738,13 +738,14 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
         int* zero = d == 128 ? (n_splits > 1 ? ints : ints + n_flags) : nullptr;
         const int n_zero = (n_splits > 1 ? n_flags : 0) + 1 + cfg.n_kv_heads;
         // The eight-wave pipelined kernel can transpose the values on their way out of LDS
-        // instead of reading a V^T copy made here.  Its loop is then ~2.5 % slower (half as
-        // many bytes per LDS instruction), the copy costs its bytes at ~5.5 TB/s plus a launch,
-        // and doing without it costs one small launch (a fill kernel for the counters that
-        // the pre-pass otherwise clears): the copy is skipped when that is the
-        // cheaper side, which it is for the user-query rows and for short launches over long
-        // caches (measured: 128 rows over 32k keys 110 -> 94 us, 1766 rows 477 -> 468 us,
-        // 6681 rows 1490 -> 1501 us, 883 rows over 4k keys 77 -> 81 us).
+        // instead of reading a V^T copy made here.  Its loop then issues half as many bytes per
+        // LDS instruction and needs ~2 % more clocks (about 1 % more time at the clock the part
+        // grants: 131k keys x 26470 rows 21.6 -> 21.8 ms); the copy costs its bytes at ~5.5 TB/s
+        // plus a launch, and doing without it costs one small launch (a fill kernel for the
+        // counters that the pre-pass otherwise clears).  The copy is skipped when that is the
+        // cheaper side, which it is for everything but the largest launches (measured, copy ->
+        // no copy: 128 rows over 32k keys 106 -> 85 us, 1766 rows 487 -> 470 us, 6681 rows
+        // 1496 -> 1486 us, 13235 rows 2785 -> 2784 us).
         bool nat_v = false;
         if (d == 128) {
             const int src = attn_dma128_v_source();
@@ -753,7 +754,7 @@ pkv_status launch_sparse_row_attn(const pkv_layer_cfg& cfg, const void* q,
                 const double copy_us = 3.0 + (double)n_pad * cfg.n_kv_heads * d * 4.0 / 5.5e6;
                 const double main_us = 1.68 * (double)ceil_div(m, bm) * cfg.n_kv_heads *
                                        (double)(n_pad / 64) * (m > 768 ? 0.5 : 1.0) / 256.0;
-                nat_v = copy_us - 4.0 > 0.025 * main_us;
+                nat_v = copy_us - 4.0 > 0.012 * main_us;
             } else {
                 nat_v = src == 0;
             }
